@@ -1,0 +1,195 @@
+/*
+ * he_fedavg.h -- C ABI of the MI355X (gfx950) library for HE-based federated aggregation.
+ *
+ * The library implements the data path of Algorithm 1 ("HE-Based Federated Aggregation")
+ * of the FedML-HE paper with an RNS-CKKS scheme over 31-bit primes:
+ *
+ *   key authority : (pk, sk) <- HE.KeyGen                                   he_keygen
+ *   client        : [W_i] <- HE.Enc(pk, M . W_i) + (1-M) . W_i              he_encrypt_masked
+ *   server        : [W_glob] <- sum_i a_i [[M . W_i]] + sum_i a_i (1-M).W_i he_aggregate
+ *   client        : W <- HE.Dec(sk, M . [W_glob]) + (1-M) . [W_glob]        he_decrypt_merge
+ *
+ * (Section "Algorithm for HE-Based Federated Aggregation"; the call names follow the table
+ * "HE Framework APIs": key_gen, enc, he_aggregate, dec.  flatten/reshape are the caller's.)
+ *
+ * Conventions
+ * -----------
+ *  - Every function returns he_status: 0 on success, negative on error.  Nothing throws,
+ *    aborts or prints.  he_last_error() returns a thread-local, library-owned message for
+ *    the most recent failing call of the calling thread.
+ *  - "dev" pointers are device (HBM) pointers on the context's GPU, "host" pointers are
+ *    ordinary host memory.  All data buffers are allocated by the caller and are never
+ *    retained after the call returns; host arrays are consumed before the call returns.
+ *  - All GPU work is enqueued on the given stream (a hipStream_t passed as void*; NULL is
+ *    the default stream).  Calls are asynchronous with respect to the host except where a
+ *    function says otherwise.  A context owns scratch memory: calls that share a context
+ *    must be issued on one stream (or be externally ordered).
+ *  - Ring: R = Z[X]/(X^N+1), N = 2^log2_n, n = N/2 slots per ciphertext (the paper's
+ *    "packing batch size").  Modulus chain q_0 > ... > q_{L-1}, primes < 2^31, q = 1 mod 2N.
+ *  - Ciphertext layout: uint32 [n_ct][2][level][N], coefficient domain, residues in [0,q_j),
+ *    poly 0 = c0, poly 1 = c1; a fresh ciphertext has level L, an aggregated one L-1.
+ *  - Masked parameters are packed in parameter order, n per ciphertext, the last ciphertext
+ *    zero padded (a vector shorter than the packing batch still takes a whole ciphertext,
+ *    Section "Results on Different Scales of Models").  The plaintext remainder (1-M).W is
+ *    kept compacted in parameter order: float32 [P - P_enc].
+ *  - Randomness: Philox4x32-10, key = seed, counter = (block, ciphertext index, client id,
+ *    stream tag); outputs are a pure function of (params, seed, client id, inputs).
+ *  - Input parameters must be finite with |x| * 2^scale_bits < 2^31 (not checked on the
+ *    hot path).
+ */
+#ifndef HE_FEDAVG_H
+#define HE_FEDAVG_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t he_status;
+enum {
+  HE_OK = 0,
+  HE_ERR_INVALID_ARG = -1,   /* null pointer, bad size, unsorted/overlapping runs, bad weights */
+  HE_ERR_LEVEL = -2,         /* ciphertext level does not fit the operation                     */
+  HE_ERR_HIP = -3,           /* a HIP runtime call failed; message carries hipGetErrorString     */
+  HE_ERR_NOMEM = -4,         /* host or device allocation failed                                 */
+  HE_ERR_UNIMPLEMENTED = -5
+};
+
+#define HE_MAX_LIMBS 8
+#define HE_MAX_CLIENTS_PER_CALL 4096
+
+typedef struct he_ctx he_ctx;    /* public crypto context: N, chain, scale, tables (device)     */
+typedef struct he_pk he_pk;      /* public key (b, a), transform domain, device                  */
+typedef struct he_sk he_sk;      /* secret key s, transform domain, device                       */
+typedef struct he_mask he_mask;  /* selective-encryption mask M as sorted runs, host + device    */
+
+typedef struct {
+  uint32_t log2_n;        /* 3..14; 13 and 14 are the tuned sizes                               */
+  uint32_t n_limbs;       /* L, 2..HE_MAX_LIMBS                                                 */
+  uint32_t scale_bits;    /* log2 of the CKKS scale Delta, 1..30                                */
+  uint32_t cbd_eta;       /* centred-binomial parameter of the error, 0..32 (0 = no error)      */
+  const uint32_t* primes; /* host, L entries descending, or NULL: the L largest primes < 2^31
+                             with q = 1 (mod 2N)                                                */
+} he_params;
+
+const char* he_last_error(void);
+
+/* ---- context (the public "crypto context" that also the server receives) -------------- */
+
+/* Creates the context on GPU `device`: derives the chain, the 2N-th roots (smallest
+   primitive root per prime), transform and encoder tables, and uploads them.  Synchronous. */
+he_status he_ctx_create(const he_params* params, int device, he_ctx** out);
+void he_ctx_destroy(he_ctx* ctx);
+/* Copies the L primes to primes_host[L]. */
+he_status he_ctx_primes(const he_ctx* ctx, uint32_t* primes_host);
+uint32_t he_ctx_ring_degree(const he_ctx* ctx);                 /* N                          */
+uint32_t he_ctx_n_limbs(const he_ctx* ctx);                     /* L                          */
+uint64_t he_ct_bytes(const he_ctx* ctx, uint32_t level);        /* 2 * level * N * 4          */
+
+/* ---- HE.KeyGen (Algorithm 1, "Key Authority Generate Key") ---------------------------- */
+
+/* s ternary, a_j uniform, e centred binomial; b_j = -(a_j * s) + e mod q_j.  Keys live on
+   the device in the transform domain.  Asynchronous on `stream`. */
+he_status he_keygen(he_ctx* ctx, uint64_t seed, he_pk** pk, he_sk** sk, void* stream);
+void he_pk_destroy(he_pk* pk);
+void he_sk_destroy(he_sk* sk);
+
+/* ---- mask M ("Selective Parameter Encryption": which entries are encrypted) ----------- */
+
+/* starts/lens: host arrays of n_runs sorted, disjoint, non-empty runs inside [0, P).
+   n_runs = 0 is the empty mask (everything stays plaintext).  Synchronous. */
+he_status he_mask_create(he_ctx* ctx, uint64_t P, const uint64_t* starts_host,
+                         const uint64_t* lens_host, uint64_t n_runs, he_mask** out);
+/* Builds the run list from a device byte mask (non-zero = encrypted).  Copies the mask to
+   the host to do so (set-up path, synchronous on `stream`). */
+he_status he_mask_from_bytes(he_ctx* ctx, uint64_t P, const uint8_t* mask_dev, he_mask** out,
+                             void* stream);
+void he_mask_destroy(he_mask* mask);
+uint64_t he_mask_n_params(const he_mask* mask);                 /* P                          */
+uint64_t he_mask_n_enc(const he_mask* mask);                    /* P_enc                      */
+uint64_t he_n_ct(const he_ctx* ctx, const he_mask* mask);       /* ceil(P_enc / n)            */
+
+/* ---- client: [W_i] <- HE.Enc(pk, M . W_i) + (1-M) . W_i (Algorithm 1, training loop) --- */
+
+/* w_dev float32[P]; ct_out_dev uint32[n_ct][2][L][N]; plain_out_dev float32[P-P_enc]
+   (may be NULL when P == P_enc).  Gathers the masked entries, encodes each block of n into
+   a plaintext polynomial at scale Delta, encrypts it under pk with the randomness stream
+   (seed, client_id, ciphertext index), and compacts the unmasked entries. */
+he_status he_encrypt_masked(he_ctx* ctx, const he_pk* pk, const he_mask* mask, uint64_t seed,
+                            uint32_t client_id, const float* w_dev, uint32_t* ct_out_dev,
+                            float* plain_out_dev, void* stream);
+
+/* ---- server: [W_glob] <- sum_i a_i [[M.W_i]] + sum_i a_i (1-M).W_i ---------------------
+   ("Server Model Aggregation"; plaintext weights, one multiplicative depth.)
+   alpha_host double[K]: alpha_i > 0, |sum - 1| <= 1e-9.  Each weight becomes the integer
+   w_i = rint(alpha_i * q_{L-1}) (ties to even); ciphertexts are multiplied by w_i, summed
+   over clients, and rescaled by q_{L-1} (round to nearest), which returns the scale to
+   Delta and drops one limb.  The plaintext remainders are averaged in float64 in client
+   order (product and sum rounded separately) and rounded once to float32.
+   ct_in_dev / plain_in_dev: host arrays of K device pointers (plain_in_dev may be NULL when
+   n_plain == 0).  ct_out_dev uint32[n_ct][2][L-1][N]; plain_out_dev float32[n_plain].
+   Needs only the public context -- no key. */
+he_status he_aggregate(he_ctx* ctx, uint32_t K, const double* alpha_host,
+                       const uint32_t* const* ct_in_dev, const float* const* plain_in_dev,
+                       uint64_t n_ct, uint64_t n_plain, uint32_t* ct_out_dev,
+                       float* plain_out_dev, void* stream);
+
+/* Streaming form of the same sum for client sets that do not fit in memory at once.
+   acc_ct_dev uint32[n_ct][2][L][N] (residues), acc_plain_dev double[n_plain]; both caller
+   owned.  begin zeroes them; add folds K_chunk more clients in (alpha_host holds their
+   globally normalised weights; clients must be added in the same order as the one-shot
+   call would see them for bit-identical plaintext sums); finalize rescales / rounds. */
+he_status he_aggregate_begin(he_ctx* ctx, uint64_t n_ct, uint64_t n_plain, uint32_t* acc_ct_dev,
+                             double* acc_plain_dev, void* stream);
+he_status he_aggregate_add(he_ctx* ctx, uint32_t K_chunk, const double* alpha_host,
+                           const uint32_t* const* ct_in_dev, const float* const* plain_in_dev,
+                           uint64_t n_ct, uint64_t n_plain, uint32_t* acc_ct_dev,
+                           double* acc_plain_dev, void* stream);
+he_status he_aggregate_finalize(he_ctx* ctx, uint64_t n_ct, uint64_t n_plain,
+                                const uint32_t* acc_ct_dev, const double* acc_plain_dev,
+                                uint32_t* ct_out_dev, float* plain_out_dev, void* stream);
+
+/* ---- client: W <- HE.Dec(sk, M . [W_glob]) + (1-M) . [W_glob] -------------------------- */
+
+/* ct_glob_dev uint32[n_ct][2][L-1][N] (level L-1); plain_glob_dev float32[P-P_enc] (may be
+   NULL when P == P_enc); w_out_dev float32[P].  Decrypts, lifts the residues to the centred
+   integer, decodes the slots, and scatters masked and unmasked entries back to their
+   parameter positions. */
+he_status he_decrypt_merge(he_ctx* ctx, const he_sk* sk, const he_mask* mask,
+                           const uint32_t* ct_glob_dev, const float* plain_glob_dev,
+                           float* w_out_dev, void* stream);
+
+/* ---- test / measurement exports (single steps of the calls above) ---------------------- */
+
+/* Slot encoding only: slots_dev float32[n_ct][n] -> m_out_dev int32[n_ct][N],
+   m_k = rint((2*Delta/N) * sum_j z_j cos(pi * 5^j * k / N)). */
+he_status he_debug_encode(he_ctx* ctx, const float* slots_dev, uint64_t n_ct, int32_t* m_out_dev,
+                          void* stream);
+/* Encryption of given integer plaintexts m_dev int32[n_ct][N] (ciphertext indices
+   first_ct .. first_ct + n_ct - 1 of client `client_id`) -> ct_out_dev uint32[n_ct][2][L][N]. */
+he_status he_debug_encrypt_plain(he_ctx* ctx, const he_pk* pk, uint64_t seed, uint32_t client_id,
+                                 uint64_t first_ct, const int32_t* m_dev, uint64_t n_ct,
+                                 uint32_t* ct_out_dev, void* stream);
+/* Decryption without decoding: ct_dev uint32[n_ct][2][level][N] -> d_out_dev
+   uint32[n_ct][level][N], d_j = c0_j + c1_j * s mod q_j. */
+he_status he_debug_decrypt_residues(he_ctx* ctx, const he_sk* sk, const uint32_t* ct_dev,
+                                    uint64_t n_ct, uint32_t level, uint32_t* d_out_dev,
+                                    void* stream);
+/* Lift + decode only: d_dev uint32[n_ct][level][N] -> slots_out_dev float64[n_ct][n]. */
+he_status he_debug_decode(he_ctx* ctx, const uint32_t* d_dev, uint64_t n_ct, uint32_t level,
+                          double* slots_out_dev, void* stream);
+/* In-place negacyclic transform of polys_dev uint32[batch][N] modulo q_limb.  Forward:
+   coefficients -> evaluations, entry i = a(psi^(2*bitrev(i)+1)); inverse undoes it
+   (including the 1/N factor). */
+he_status he_debug_ntt(he_ctx* ctx, int inverse, uint32_t limb, uint32_t* polys_dev,
+                       uint64_t batch, void* stream);
+/* Keys in the coefficient domain for comparison with a reference: pk_coeff_dev
+   uint32[2][L][N] (b then a), sk_coeff_dev int32[N] in {-1,0,1}.  Either may be NULL. */
+he_status he_debug_export_keys(he_ctx* ctx, const he_pk* pk, const he_sk* sk,
+                               uint32_t* pk_coeff_dev, int32_t* sk_coeff_dev, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HE_FEDAVG_H */

@@ -1,0 +1,1286 @@
+// MI355X (gfx950) library for HE-based federated aggregation: kernels and C ABI.
+// See include/he_fedavg.h for the contract of every entry point.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "he_device.hpp"
+#include "he_fedavg.h"
+#include "he_host_tables.hpp"
+
+using namespace he;
+
+namespace {
+
+// =========================================================================================
+// Device-visible descriptors (passed to kernels by value)
+// =========================================================================================
+
+struct RingDev {
+  uint32_t logN, N, L, scale_bits, eta;
+  uint32_t q[kMaxLimbs];
+  uint2 ninv[kMaxLimbs];     // N^-1 mod q_j (+ Shoup companion)
+  const uint2* tw_fwd;       // [L][N]  psi^bitrev(k)
+  const uint2* tw_inv;       // [L][N]  psi^-bitrev(k)
+  const double2* fft_e;      // [n/2]   exp(-2 pi i r / n)
+  const double2* twist;      // [n]     exp(+i pi k / N)
+  const uint32_t* perm_enc;  // [n]     bitrev(t_j): where slot j enters the encoder FFT
+  const uint32_t* perm_dec;  // [n]     t_j: where slot j leaves the decoder FFT
+  const uint2* garner_inv;   // [kMaxLimbs * kMaxLimbs]: entry i*kMaxLimbs+j = q_i^-1 mod q_j, i < j
+};
+
+struct MaskDev {
+  const uint64_t* start;    // [n_runs]     first parameter index of each masked run
+  const uint64_t* prefix;   // [n_runs + 1] packed offset of each masked run
+  const uint64_t* cstart;   // [n_cruns]    complement runs
+  const uint64_t* cprefix;  // [n_cruns + 1]
+  uint32_t n_runs, n_cruns;
+  uint64_t P, P_enc;
+};
+
+struct CrtArgs {
+  uint32_t qw[kMaxLimbs];  // little-endian words of Q' = prod_{j<level} q_j
+  uint32_t hw[kMaxLimbs];  // words of (Q' - 1) / 2
+};
+
+constexpr int kAggClients = 32;  // clients folded per aggregation launch
+
+struct AggArgs {
+  const uint32_t* ct[kAggClients];
+  uint32_t w[kAggClients][kMaxLimbs];  // w_i mod q_j
+  uint32_t K;
+};
+
+struct AggConst {
+  uint32_t q[kMaxLimbs];
+  uint2 c32[kMaxLimbs];    // 2^32 mod q_j
+  uint2 qlinv[kMaxLimbs];  // q_{L-1}^-1 mod q_j
+  uint32_t qdiff[kMaxLimbs];  // q_j - q_{L-1}
+  uint32_t half_last;      // (q_{L-1} - 1) / 2
+};
+
+struct PlainArgs {
+  const float* w[kAggClients];
+  double alpha[kAggClients];
+  uint32_t K;
+};
+
+// =========================================================================================
+// Kernels
+// =========================================================================================
+
+__device__ __forceinline__ uint64_t run_lookup(const uint64_t* __restrict__ start,
+                                               const uint64_t* __restrict__ prefix, uint32_t n_runs,
+                                               uint64_t t) {
+  uint32_t lo = 0, hi = n_runs;
+  while (hi - lo > 1) {
+    const uint32_t mid = (lo + hi) >> 1;
+    if (prefix[mid] <= t) lo = mid;
+    else hi = mid;
+  }
+  return start[lo] + (t - prefix[lo]);
+}
+
+// ---- a1 + a2: gather under the mask and encode one ciphertext's slots -------------------
+// m_k + i m_{k+n} = Delta * zeta^-k * (1/n) * sum_j z_j exp(-2 pi i t_j k / n)
+__global__ void __launch_bounds__(1024)
+k_encode(RingDev rg, MaskDev mk, const float* __restrict__ w, const float* __restrict__ slots_direct,
+         uint64_t first_ct, int32_t* __restrict__ m_out) {
+  extern __shared__ double lds_d[];
+  const int logn = (int)rg.logN - 1;
+  const int n = 1 << logn;
+  double* re = lds_d;
+  double* im = lds_d + n;
+  const uint64_t c_local = blockIdx.x;
+  const uint64_t c = first_ct + c_local;
+  for (int j = threadIdx.x; j < n; j += blockDim.x) {
+    double z = 0.0;
+    if (slots_direct) {
+      z = (double)slots_direct[c_local * n + j];
+    } else {
+      const uint64_t t = c * (uint64_t)n + (uint64_t)j;
+      if (t < mk.P_enc) z = (double)w[run_lookup(mk.start, mk.prefix, mk.n_runs, t)];
+    }
+    const uint32_t pos = rg.perm_enc[j];
+    re[pos] = z;
+    im[pos] = 0.0;
+  }
+  __syncthreads();
+  fft_dit_lds(re, im, logn, rg.fft_e, false);
+  const double scale = ldexp(1.0, (int)rg.scale_bits - logn);
+  int32_t* out = m_out + c_local * rg.N;
+  for (int k = threadIdx.x; k < n; k += blockDim.x) {
+    const double2 tw = rg.twist[k];
+    const double ar = re[k], ai = im[k];
+    const double cr = (ar * tw.x + ai * tw.y) * scale;
+    const double ci = (ai * tw.x - ar * tw.y) * scale;
+    out[k] = __double2int_rn(cr);
+    out[k + n] = __double2int_rn(ci);
+  }
+}
+
+// ---- a3: ephemeral randomness of one ciphertext -----------------------------------------
+// u (ternary) and e1 (CBD) as int8, e0 (CBD) added to the plaintext: me0 = m + e0.
+__global__ void __launch_bounds__(256)
+k_sample(RingDev rg, uint2 key, uint32_t client, uint64_t first_ct, const int32_t* __restrict__ m_in,
+         int32_t* __restrict__ me0, int8_t* __restrict__ u_out, int8_t* __restrict__ e1_out) {
+  const uint64_t c_local = blockIdx.x;
+  const RngKey rk{key, (uint32_t)(first_ct + c_local), client};
+  const uint32_t N = rg.N;
+  const uint32_t mask = rg.eta == 0 ? 0u : cbd_mask(rg.eta);
+  uint32_t* u32 = reinterpret_cast<uint32_t*>(u_out + c_local * N);
+  uint32_t* e32 = reinterpret_cast<uint32_t*>(e1_out + c_local * N);
+  const int2* m2 = reinterpret_cast<const int2*>(m_in + c_local * N);
+  int2* o2 = reinterpret_cast<int2*>(me0 + c_local * N);
+  for (uint32_t b = threadIdx.x; b < N / 4; b += blockDim.x) {
+    const uint4 r = rng_block(rk, b, kTagU);
+    const uint32_t p = (uint32_t)(uint8_t)ternary_from_word(r.x) | ((uint32_t)(uint8_t)ternary_from_word(r.y) << 8) |
+                       ((uint32_t)(uint8_t)ternary_from_word(r.z) << 16) | ((uint32_t)(uint8_t)ternary_from_word(r.w) << 24);
+    u32[b] = p;
+    const uint4 r0 = rng_block(rk, 2 * b, kTagE1), r1 = rng_block(rk, 2 * b + 1, kTagE1);
+    const uint32_t pe = (uint32_t)(uint8_t)cbd_from_words(r0.x, r0.y, mask) | ((uint32_t)(uint8_t)cbd_from_words(r0.z, r0.w, mask) << 8) |
+                        ((uint32_t)(uint8_t)cbd_from_words(r1.x, r1.y, mask) << 16) | ((uint32_t)(uint8_t)cbd_from_words(r1.z, r1.w, mask) << 24);
+    e32[b] = pe;
+  }
+  for (uint32_t b = threadIdx.x; b < N / 2; b += blockDim.x) {
+    const uint4 r = rng_block(rk, b, kTagE0);
+    int2 m = m2[b];
+    m.x += cbd_from_words(r.x, r.y, mask);
+    m.y += cbd_from_words(r.z, r.w, mask);
+    o2[b] = m;
+  }
+}
+
+// ---- a4: public-key encryption of one (ciphertext, limb) --------------------------------
+// c0 = INTT(b^ . NTT(u)) + (m + e0),  c1 = INTT(a^ . NTT(u)) + e1   (mod q_j)
+// pk holds b^ and a^ premultiplied by 1/N, with Shoup companions.
+__global__ void __launch_bounds__(1024)
+k_encrypt(RingDev rg, const uint2* __restrict__ pk, const int8_t* __restrict__ u, const int32_t* __restrict__ me0,
+          const int8_t* __restrict__ e1, uint32_t* __restrict__ ct_out) {
+  extern __shared__ uint32_t lds_u[];
+  const int logN = (int)rg.logN;
+  const uint32_t N = rg.N, L = rg.L;
+  const uint32_t j = blockIdx.x;
+  const uint64_t c = blockIdx.y;
+  const uint32_t q = rg.q[j];
+  uint32_t* bufU = lds_u;
+  uint32_t* bufW = lds_u + lds_pad((int)N);
+  const int8_t* uc = u + c * N;
+  ntt_forward_to_lds(bufU, logN, rg.tw_fwd + (size_t)j * N, q, [=](int a) {
+    const int v = uc[a];
+    return (uint32_t)(v < 0 ? v + (int)q : v);
+  });
+  const int32_t* mc = me0 + c * N;
+  const int8_t* ec = e1 + c * N;
+  for (uint32_t p = 0; p < 2; ++p) {
+    const uint2* key = pk + ((size_t)p * L + j) * N;
+    uint32_t* out = ct_out + ((c * 2 + p) * L + j) * N;
+    if (p == 0) {
+      ntt_inverse_from(
+          bufW, logN, rg.tw_inv + (size_t)j * N, q, [=](int a) { return mul_shoup(bufU[lds_pad(a)], key[a], q); },
+          [=](int a, uint32_t v) { out[a] = add_mod(v, residue_of_signed(mc[a], q), q); });
+    } else {
+      ntt_inverse_from(
+          bufW, logN, rg.tw_inv + (size_t)j * N, q, [=](int a) { return mul_shoup(bufU[lds_pad(a)], key[a], q); },
+          [=](int a, uint32_t v) { out[a] = add_mod(v, residue_of_signed((int32_t)ec[a], q), q); });
+    }
+    __syncthreads();
+  }
+}
+
+// ---- a8: decryption of one (ciphertext, limb): d = c0 + INTT(s^ . NTT(c1)) ----------------
+__global__ void __launch_bounds__(1024)
+k_decrypt(RingDev rg, const uint2* __restrict__ sk, const uint32_t* __restrict__ ct, uint32_t level,
+          uint32_t* __restrict__ d_out) {
+  extern __shared__ uint32_t lds_u[];
+  const int logN = (int)rg.logN;
+  const uint32_t N = rg.N;
+  const uint32_t j = blockIdx.x;
+  const uint64_t c = blockIdx.y;
+  const uint32_t q = rg.q[j];
+  const uint32_t* c0 = ct + ((c * 2 + 0) * level + j) * N;
+  const uint32_t* c1 = ct + ((c * 2 + 1) * level + j) * N;
+  uint32_t* out = d_out + (c * level + j) * N;
+  const uint2* key = sk + (size_t)j * N;
+  uint32_t* buf = lds_u;
+  ntt_forward_to_lds(buf, logN, rg.tw_fwd + (size_t)j * N, q, [=](int a) { return c1[a]; });
+  ntt_inverse_from(
+      buf, logN, rg.tw_inv + (size_t)j * N, q, [=](int a) { return mul_shoup(buf[lds_pad(a)], key[a], q); },
+      [=](int a, uint32_t v) { out[a] = add_mod(v, c0[a], q); });
+}
+
+// ---- a9: CRT lift (Garner), exact centring, conversion to fp64 ---------------------------
+template <int LEVEL>
+__device__ __forceinline__ double crt_centered(const RingDev& rg, const CrtArgs& ca, const uint32_t (&res)[LEVEL]) {
+  uint32_t x[LEVEL];  // mixed-radix digits: v = x0 + q0 (x1 + q1 (x2 + ...))
+#pragma unroll
+  for (int j = 0; j < LEVEL; ++j) {
+    const uint32_t qj = rg.q[j];
+    uint32_t t = res[j];
+#pragma unroll
+    for (int i = 0; i < j; ++i) {
+      t = sub_mod(t, csub(x[i], qj), qj);
+      t = mul_shoup(t, rg.garner_inv[i * kMaxLimbs + j], qj);
+    }
+    x[j] = t;
+  }
+  uint32_t wds[LEVEL];
+#pragma unroll
+  for (int i = 0; i < LEVEL; ++i) wds[i] = 0;
+  wds[0] = x[LEVEL - 1];
+#pragma unroll
+  for (int j = LEVEL - 2; j >= 0; --j) {
+    uint64_t carry = x[j];
+#pragma unroll
+    for (int i = 0; i < LEVEL; ++i) {
+      const uint64_t t = (uint64_t)wds[i] * rg.q[j] + carry;
+      wds[i] = (uint32_t)t;
+      carry = t >> 32;
+    }
+  }
+  // v > (Q'-1)/2 ?  compare from the top word down
+  bool greater = false, decided = false;
+#pragma unroll
+  for (int i = LEVEL - 1; i >= 0; --i) {
+    if (!decided && wds[i] != ca.hw[i]) {
+      greater = wds[i] > ca.hw[i];
+      decided = true;
+    }
+  }
+  if (greater) {  // v - Q' is negative: magnitude Q' - v
+    uint64_t borrow = 0;
+#pragma unroll
+    for (int i = 0; i < LEVEL; ++i) {
+      const uint64_t t = (uint64_t)ca.qw[i] - wds[i] - borrow;
+      wds[i] = (uint32_t)t;
+      borrow = (t >> 32) & 1;
+    }
+  }
+  double r = 0.0;
+#pragma unroll
+  for (int i = LEVEL - 1; i >= 0; --i) r = r * 4294967296.0 + (double)wds[i];
+  return greater ? -r : r;
+}
+
+// ---- a9 + a10: lift, decode, scatter one ciphertext ---------------------------------------
+// z_j = Re( sum_k (v_k + i v_{k+n}) zeta^k exp(+2 pi i t_j k / n) ) / Delta
+template <int LEVEL>
+__global__ void __launch_bounds__(1024)
+k_decode(RingDev rg, CrtArgs ca, MaskDev mk, const uint32_t* __restrict__ d, uint64_t first_ct,
+         float* __restrict__ w_out, double* __restrict__ slots_out) {
+  extern __shared__ double lds_d[];
+  const int logn = (int)rg.logN - 1;
+  const int n = 1 << logn;
+  const uint32_t N = rg.N;
+  double* re = lds_d;
+  double* im = lds_d + n;
+  const uint64_t c_local = blockIdx.x;
+  const uint32_t* dc = d + c_local * LEVEL * N;
+  for (int k = threadIdx.x; k < n; k += blockDim.x) {
+    uint32_t ra[LEVEL], rb[LEVEL];
+#pragma unroll
+    for (int j = 0; j < LEVEL; ++j) {
+      ra[j] = dc[(size_t)j * N + k];
+      rb[j] = dc[(size_t)j * N + k + n];
+    }
+    const double vr = crt_centered<LEVEL>(rg, ca, ra);
+    const double vi = crt_centered<LEVEL>(rg, ca, rb);
+    const double2 tw = rg.twist[k];
+    const uint32_t pos = bitrev((uint32_t)k, logn);
+    re[pos] = vr * tw.x - vi * tw.y;
+    im[pos] = vr * tw.y + vi * tw.x;
+  }
+  __syncthreads();
+  fft_dit_lds(re, im, logn, rg.fft_e, true);
+  const double inv_delta = ldexp(1.0, -(int)rg.scale_bits);
+  for (int j = threadIdx.x; j < n; j += blockDim.x) {
+    const double z = re[rg.perm_dec[j]] * inv_delta;
+    if (slots_out) {
+      slots_out[c_local * n + j] = z;
+    } else {
+      const uint64_t t = (first_ct + c_local) * (uint64_t)n + (uint64_t)j;
+      if (t < mk.P_enc) w_out[run_lookup(mk.start, mk.prefix, mk.n_runs, t)] = (float)z;
+    }
+  }
+}
+
+// ---- plaintext remainder: compaction (client, before sending) and scatter (after) -------
+template <bool SCATTER>
+__global__ void __launch_bounds__(256)
+k_plain_move(MaskDev mk, const float* __restrict__ src, float* __restrict__ dst) {
+  const uint64_t n_plain = mk.P - mk.P_enc;
+  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+  for (uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; t < n_plain; t += stride) {
+    const uint64_t idx = run_lookup(mk.cstart, mk.cprefix, mk.n_cruns, t);
+    if (SCATTER) dst[idx] = src[t];
+    else dst[t] = src[idx];
+  }
+}
+
+// ---- a5 + a6: sum_i w_i ct_i (mod q_j) over clients, then rescale by q_{L-1} ---------------
+// One thread owns 4 consecutive coefficients of one (ciphertext, poly) in all L limbs.
+// Products w*x < 2^62 are accumulated in 64 bits and folded back below q every 4 terms.
+__device__ __forceinline__ uint32_t reduce64(uint64_t x, uint2 c32, uint32_t q) {
+  const uint32_t hi = (uint32_t)(x >> 32), lo = (uint32_t)x;
+  const uint32_t t = mul_shoup(hi, c32, q);          // hi * 2^32 mod q
+  return add_mod(t, csub(csub(lo, q), q), q);        // lo < 2^32 < 3q
+}
+
+template <int L, bool HAS_ACC, bool FINAL>
+__global__ void __launch_bounds__(256)
+k_aggregate(AggArgs a, AggConst k, uint32_t log_n4, uint64_t n_vec, const uint4* __restrict__ acc_in,
+            uint4* __restrict__ out) {
+  const uint64_t gid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= n_vec) return;
+  const uint64_t cp = gid >> log_n4;                 // ciphertext * 2 + poly
+  const uint64_t kk = gid & ((1ull << log_n4) - 1);  // which group of 4 coefficients
+  uint32_t res[L][4];
+#pragma unroll
+  for (int j = L - 1; j >= 0; --j) {
+    const uint64_t off = ((cp * L + j) << log_n4) + kk;
+    const uint32_t q = k.q[j];
+    uint64_t acc[4] = {0, 0, 0, 0};
+    if (HAS_ACC) {
+      const uint4 v = acc_in[off];
+      acc[0] = v.x; acc[1] = v.y; acc[2] = v.z; acc[3] = v.w;
+    }
+    for (uint32_t i = 0; i < a.K; ++i) {
+      const uint4 x = reinterpret_cast<const uint4*>(a.ct[i])[off];
+      const uint64_t w = a.w[i][j];
+      acc[0] += w * x.x; acc[1] += w * x.y; acc[2] += w * x.z; acc[3] += w * x.w;
+      if ((i & 3) == 3) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] = reduce64(acc[e], k.c32[j], q);
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) res[j][e] = reduce64(acc[e], k.c32[j], q);
+    if (!FINAL) out[off] = make_uint4(res[j][0], res[j][1], res[j][2], res[j][3]);
+  }
+  if (FINAL) {
+#pragma unroll
+    for (int j = 0; j < L - 1; ++j) {
+      const uint32_t q = k.q[j];
+      uint32_t o[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t r = res[L - 1][e];
+        const uint32_t rj = r > k.half_last ? r + k.qdiff[j] : r;  // centred residue, reduced mod q_j
+        o[e] = mul_shoup(sub_mod(res[j][e], rj, q), k.qlinv[j], q);
+      }
+      out[((cp * (L - 1) + j) << log_n4) + kk] = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+  }
+}
+
+// ---- a7: plain FedAvg of the unmasked remainder -------------------------------------------
+// acc <- acc + alpha_i * w_i in float64, product and sum rounded separately, client order.
+template <bool HAS_ACC, bool FINAL>
+__global__ void __launch_bounds__(256)
+k_plain_fedavg(PlainArgs a, uint64_t n_plain, const double* __restrict__ acc_in, double* __restrict__ acc_out,
+               float* __restrict__ out) {
+  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+  for (uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; t < n_plain; t += stride) {
+    double acc = HAS_ACC ? acc_in[t] : 0.0;
+    for (uint32_t i = 0; i < a.K; ++i) acc = __dadd_rn(acc, __dmul_rn(a.alpha[i], (double)a.w[i][t]));
+    if (FINAL) out[t] = (float)acc;
+    else acc_out[t] = acc;
+  }
+}
+
+__global__ void __launch_bounds__(256) k_fill_u32(uint32_t* p, uint64_t n, uint32_t v) {
+  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+  for (uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; t < n; t += stride) p[t] = v;
+}
+
+// ---- standalone batched transform (debug export, key generation) ------------------------
+// limb < 0: polynomial b uses limb b % L (for [..][L][N] layouts).
+template <bool INV>
+__global__ void __launch_bounds__(1024)
+k_ntt_batch(RingDev rg, int limb, uint32_t* __restrict__ polys) {
+  extern __shared__ uint32_t lds_u[];
+  const int logN = (int)rg.logN;
+  const uint32_t N = rg.N;
+  const uint32_t j = limb >= 0 ? (uint32_t)limb : (uint32_t)(blockIdx.x % rg.L);
+  const uint32_t q = rg.q[j];
+  uint32_t* x = polys + (size_t)blockIdx.x * N;
+  uint32_t* buf = lds_u;
+  if (!INV) {
+    ntt_forward_to_lds(buf, logN, rg.tw_fwd + (size_t)j * N, q, [=](int a) { return x[a]; });
+    for (uint32_t a = threadIdx.x; a < N; a += blockDim.x) x[a] = buf[lds_pad((int)a)];
+  } else {
+    const uint2 ninv = rg.ninv[j];
+    ntt_inverse_from(
+        buf, logN, rg.tw_inv + (size_t)j * N, q, [=](int a) { return x[a]; },
+        [=](int a, uint32_t v) { x[a] = mul_shoup(v, ninv, q); });
+  }
+}
+
+// ---- key generation ---------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_keygen_sample(RingDev rg, uint2 key, int8_t* __restrict__ s_coeff, uint32_t* __restrict__ s_res,
+                uint32_t* __restrict__ e_res, uint32_t* __restrict__ a_res) {
+  const uint32_t kidx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (kidx >= rg.N) return;
+  const RngKey rk{key, 0u, 0u};
+  const uint32_t mask = rg.eta == 0 ? 0u : cbd_mask(rg.eta);
+  const uint4 rs = rng_block(rk, kidx >> 2, kTagS);
+  const uint32_t ws[4] = {rs.x, rs.y, rs.z, rs.w};
+  const int s = ternary_from_word(ws[kidx & 3]);
+  const uint4 re = rng_block(rk, kidx >> 1, kTagEpk);
+  const int e = (kidx & 1) ? cbd_from_words(re.z, re.w, mask) : cbd_from_words(re.x, re.y, mask);
+  s_coeff[kidx] = (int8_t)s;
+  for (uint32_t j = 0; j < rg.L; ++j) {
+    const uint32_t q = rg.q[j];
+    s_res[(size_t)j * rg.N + kidx] = residue_of_signed(s, q);
+    e_res[(size_t)j * rg.N + kidx] = residue_of_signed(e, q);
+    const uint4 ra = rng_block(rk, kidx >> 1, kTagA0 + j);
+    const uint64_t x = (kidx & 1) ? (((uint64_t)ra.w << 32) | ra.z) : (((uint64_t)ra.y << 32) | ra.x);
+    a_res[(size_t)j * rg.N + kidx] = (uint32_t)(x % q);
+  }
+}
+
+// b^ = e^ - a^ . s^ ; tables premultiplied by 1/N with Shoup companions.
+__global__ void __launch_bounds__(256)
+k_keygen_combine(RingDev rg, const uint32_t* __restrict__ s_hat, const uint32_t* __restrict__ e_hat,
+                 const uint32_t* __restrict__ a_hat, uint32_t* __restrict__ pk_raw, uint2* __restrict__ pk_tab,
+                 uint2* __restrict__ sk_tab) {
+  const uint32_t kidx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (kidx >= rg.N) return;
+  const uint32_t N = rg.N, L = rg.L;
+  for (uint32_t j = 0; j < L; ++j) {
+    const uint32_t q = rg.q[j];
+    const size_t o = (size_t)j * N + kidx;
+    const uint32_t s = s_hat[o], a = a_hat[o], e = e_hat[o];
+    const uint32_t as = (uint32_t)((uint64_t)a * s % q);
+    const uint32_t b = sub_mod(e, as, q);
+    pk_raw[o] = b;
+    pk_raw[(size_t)L * N + o] = a;
+    const uint32_t bn = mul_shoup(b, rg.ninv[j], q), an = mul_shoup(a, rg.ninv[j], q), sn = mul_shoup(s, rg.ninv[j], q);
+    pk_tab[o] = make_uint2(bn, (uint32_t)(((uint64_t)bn << 32) / q));
+    pk_tab[(size_t)L * N + o] = make_uint2(an, (uint32_t)(((uint64_t)an << 32) / q));
+    sk_tab[o] = make_uint2(sn, (uint32_t)(((uint64_t)sn << 32) / q));
+  }
+}
+
+__global__ void __launch_bounds__(256) k_widen_i8(const int8_t* __restrict__ in, int32_t* __restrict__ out, uint32_t n) {
+  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = in[i];
+}
+
+// =========================================================================================
+// Host side
+// =========================================================================================
+
+thread_local std::string g_last_error;
+
+he_status fail(he_status code, const std::string& msg) {
+  g_last_error = msg;
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                         \
+  do {                                                                                        \
+    hipError_t e_ = (expr);                                                                   \
+    if (e_ != hipSuccess)                                                                     \
+      return fail(e_ == hipErrorOutOfMemory ? HE_ERR_NOMEM : HE_ERR_HIP,                      \
+                  std::string(#expr) + ": " + hipGetErrorString(e_));                         \
+  } while (0)
+
+constexpr uint64_t kCtChunk = 1024;  // ciphertexts per scratch chunk
+
+}  // namespace
+
+struct he_ctx {
+  int device = 0;
+  RingDev ring{};
+  std::vector<uint32_t> primes;
+  std::vector<void*> dev_allocs;
+  AggConst agg{};
+  void* ws = nullptr;  // scratch, grown on demand
+  size_t ws_bytes = 0;
+  int max_lds = 0;
+};
+
+struct he_pk {
+  he_ctx* ctx;
+  uint2* tab;     // [2][L][N] (b^, a^) * 1/N with Shoup companions
+  uint32_t* raw;  // [2][L][N] (b^, a^) as they are
+};
+
+struct he_sk {
+  he_ctx* ctx;
+  uint2* tab;     // [L][N] s^ * 1/N with Shoup companions
+  int8_t* coeff;  // [N] s in {-1,0,1}
+};
+
+struct he_mask {
+  he_ctx* ctx;
+  MaskDev dev{};
+  void* dev_block = nullptr;
+};
+
+namespace {
+
+he_status ensure_ws(he_ctx* ctx, size_t bytes) {
+  if (ctx->ws_bytes >= bytes) return HE_OK;
+  if (ctx->ws) {
+    HIP_TRY(hipDeviceSynchronize());  // earlier launches may still use the old block
+    HIP_TRY(hipFree(ctx->ws));
+    ctx->ws = nullptr;
+    ctx->ws_bytes = 0;
+  }
+  HIP_TRY(hipMalloc(&ctx->ws, bytes));
+  ctx->ws_bytes = bytes;
+  return HE_OK;
+}
+
+template <class T>
+he_status upload(he_ctx* ctx, const std::vector<T>& host, const T** dev_out) {
+  void* p = nullptr;
+  HIP_TRY(hipMalloc(&p, std::max<size_t>(host.size() * sizeof(T), 16)));
+  ctx->dev_allocs.push_back(p);
+  if (!host.empty()) HIP_TRY(hipMemcpy(p, host.data(), host.size() * sizeof(T), hipMemcpyHostToDevice));
+  *dev_out = static_cast<const T*>(p);
+  return HE_OK;
+}
+
+int ntt_threads(uint32_t N) { return (int)std::min<uint32_t>(1024, std::max<uint32_t>(64, N >> 4)); }
+int fft_threads(uint32_t n) { return (int)std::min<uint32_t>(1024, std::max<uint32_t>(64, n >> 2)); }
+size_t ntt_lds_bytes(uint32_t N, int bufs) { return (size_t)bufs * lds_pad((int)N) * sizeof(uint32_t); }
+size_t fft_lds_bytes(uint32_t n) { return (size_t)2 * n * sizeof(double); }
+
+template <class K>
+he_status allow_lds(K kernel, size_t bytes) {
+  HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+  return HE_OK;
+}
+
+uint32_t grid_for(uint64_t n, uint32_t block, uint32_t cap = 1u << 20) {
+  return (uint32_t)std::min<uint64_t>(cap, std::max<uint64_t>(1, (n + block - 1) / block));
+}
+
+he_status check_ctx(const he_ctx* ctx) {
+  if (!ctx) return fail(HE_ERR_INVALID_ARG, "context is null");
+  HIP_TRY(hipSetDevice(ctx->device));
+  return HE_OK;
+}
+
+// ---- shared launch helpers ---------------------------------------------------------------
+
+he_status launch_encode(he_ctx* ctx, const MaskDev& mk, const float* w, const float* slots, uint64_t first_ct,
+                        uint64_t n_ct, int32_t* m_out, hipStream_t st) {
+  const uint32_t n = ctx->ring.N / 2;
+  hipLaunchKernelGGL(k_encode, dim3((uint32_t)n_ct), dim3(fft_threads(n)), fft_lds_bytes(n), st, ctx->ring, mk, w, slots,
+                     first_ct, m_out);
+  HIP_TRY(hipGetLastError());
+  return HE_OK;
+}
+
+he_status launch_sample_encrypt(he_ctx* ctx, const he_pk* pk, uint64_t seed, uint32_t client, uint64_t first_ct,
+                                uint64_t n_ct, const int32_t* m_in, int32_t* me0, int8_t* u, int8_t* e1,
+                                uint32_t* ct_out, hipStream_t st) {
+  const RingDev& rg = ctx->ring;
+  const uint2 key = make_uint2((uint32_t)seed, (uint32_t)(seed >> 32));
+  hipLaunchKernelGGL(k_sample, dim3((uint32_t)n_ct), dim3(256), 0, st, rg, key, client, first_ct, m_in, me0, u, e1);
+  HIP_TRY(hipGetLastError());
+  hipLaunchKernelGGL(k_encrypt, dim3(rg.L, (uint32_t)n_ct), dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 2), st, rg,
+                     pk->tab, u, me0, e1, ct_out);
+  HIP_TRY(hipGetLastError());
+  return HE_OK;
+}
+
+he_status launch_decrypt(he_ctx* ctx, const he_sk* sk, const uint32_t* ct, uint64_t n_ct, uint32_t level, uint32_t* d_out,
+                         hipStream_t st) {
+  const RingDev& rg = ctx->ring;
+  hipLaunchKernelGGL(k_decrypt, dim3(level, (uint32_t)n_ct), dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 1), st, rg,
+                     sk->tab, ct, level, d_out);
+  HIP_TRY(hipGetLastError());
+  return HE_OK;
+}
+
+template <int LEVEL>
+void launch_decode_t(he_ctx* ctx, const CrtArgs& ca, const MaskDev& mk, const uint32_t* d, uint64_t first_ct, uint64_t n_ct,
+                     float* w_out, double* slots_out, hipStream_t st) {
+  const uint32_t n = ctx->ring.N / 2;
+  hipLaunchKernelGGL(k_decode<LEVEL>, dim3((uint32_t)n_ct), dim3(fft_threads(n)), fft_lds_bytes(n), st, ctx->ring, ca, mk, d,
+                     first_ct, w_out, slots_out);
+}
+
+he_status launch_decode(he_ctx* ctx, uint32_t level, const MaskDev& mk, const uint32_t* d, uint64_t first_ct, uint64_t n_ct,
+                        float* w_out, double* slots_out, hipStream_t st) {
+  CrtArgs ca{};
+  he_host::modulus_words(ctx->primes.data(), level, ca.qw, ca.hw);
+  switch (level) {
+    case 1: launch_decode_t<1>(ctx, ca, mk, d, first_ct, n_ct, w_out, slots_out, st); break;
+    case 2: launch_decode_t<2>(ctx, ca, mk, d, first_ct, n_ct, w_out, slots_out, st); break;
+    case 3: launch_decode_t<3>(ctx, ca, mk, d, first_ct, n_ct, w_out, slots_out, st); break;
+    case 4: launch_decode_t<4>(ctx, ca, mk, d, first_ct, n_ct, w_out, slots_out, st); break;
+    case 5: launch_decode_t<5>(ctx, ca, mk, d, first_ct, n_ct, w_out, slots_out, st); break;
+    case 6: launch_decode_t<6>(ctx, ca, mk, d, first_ct, n_ct, w_out, slots_out, st); break;
+    case 7: launch_decode_t<7>(ctx, ca, mk, d, first_ct, n_ct, w_out, slots_out, st); break;
+    case 8: launch_decode_t<8>(ctx, ca, mk, d, first_ct, n_ct, w_out, slots_out, st); break;
+    default: return fail(HE_ERR_LEVEL, "level out of range");
+  }
+  HIP_TRY(hipGetLastError());
+  return HE_OK;
+}
+
+template <int L, bool HAS_ACC, bool FINAL>
+void launch_agg_t(const AggArgs& a, const AggConst& k, uint32_t log_n4, uint64_t n_vec, const uint32_t* acc_in, uint32_t* out,
+                  hipStream_t st) {
+  hipLaunchKernelGGL((k_aggregate<L, HAS_ACC, FINAL>), dim3((uint32_t)((n_vec + 255) / 256)), dim3(256), 0, st, a, k, log_n4,
+                     n_vec, reinterpret_cast<const uint4*>(acc_in), reinterpret_cast<uint4*>(out));
+}
+
+template <int L>
+void launch_agg_l(bool has_acc, bool fin, const AggArgs& a, const AggConst& k, uint32_t log_n4, uint64_t n_vec,
+                  const uint32_t* acc_in, uint32_t* out, hipStream_t st) {
+  if (has_acc && fin) launch_agg_t<L, true, true>(a, k, log_n4, n_vec, acc_in, out, st);
+  else if (has_acc) launch_agg_t<L, true, false>(a, k, log_n4, n_vec, acc_in, out, st);
+  else if (fin) launch_agg_t<L, false, true>(a, k, log_n4, n_vec, acc_in, out, st);
+  else launch_agg_t<L, false, false>(a, k, log_n4, n_vec, acc_in, out, st);
+}
+
+he_status launch_agg(he_ctx* ctx, bool has_acc, bool fin, const AggArgs& a, uint64_t n_ct, const uint32_t* acc_in,
+                     uint32_t* out, hipStream_t st) {
+  if (n_ct == 0) return HE_OK;
+  const RingDev& rg = ctx->ring;
+  const uint32_t log_n4 = rg.logN - 2;
+  const uint64_t n_vec = (n_ct * 2) << log_n4;
+  if (((n_vec + 255) / 256) > 0x7FFFFFFFull) return fail(HE_ERR_INVALID_ARG, "too many ciphertexts for one launch");
+  switch (rg.L) {
+    case 2: launch_agg_l<2>(has_acc, fin, a, ctx->agg, log_n4, n_vec, acc_in, out, st); break;
+    case 3: launch_agg_l<3>(has_acc, fin, a, ctx->agg, log_n4, n_vec, acc_in, out, st); break;
+    case 4: launch_agg_l<4>(has_acc, fin, a, ctx->agg, log_n4, n_vec, acc_in, out, st); break;
+    case 5: launch_agg_l<5>(has_acc, fin, a, ctx->agg, log_n4, n_vec, acc_in, out, st); break;
+    case 6: launch_agg_l<6>(has_acc, fin, a, ctx->agg, log_n4, n_vec, acc_in, out, st); break;
+    case 7: launch_agg_l<7>(has_acc, fin, a, ctx->agg, log_n4, n_vec, acc_in, out, st); break;
+    case 8: launch_agg_l<8>(has_acc, fin, a, ctx->agg, log_n4, n_vec, acc_in, out, st); break;
+    default: return fail(HE_ERR_INVALID_ARG, "unsupported limb count");
+  }
+  HIP_TRY(hipGetLastError());
+  return HE_OK;
+}
+
+he_status launch_plain(bool has_acc, bool fin, const PlainArgs& a, uint64_t n_plain, const double* acc_in, double* acc_out,
+                       float* out, hipStream_t st) {
+  if (n_plain == 0) return HE_OK;
+  const dim3 grid(grid_for(n_plain, 256)), block(256);
+  if (has_acc && fin) hipLaunchKernelGGL((k_plain_fedavg<true, true>), grid, block, 0, st, a, n_plain, acc_in, acc_out, out);
+  else if (has_acc) hipLaunchKernelGGL((k_plain_fedavg<true, false>), grid, block, 0, st, a, n_plain, acc_in, acc_out, out);
+  else if (fin) hipLaunchKernelGGL((k_plain_fedavg<false, true>), grid, block, 0, st, a, n_plain, acc_in, acc_out, out);
+  else hipLaunchKernelGGL((k_plain_fedavg<false, false>), grid, block, 0, st, a, n_plain, acc_in, acc_out, out);
+  HIP_TRY(hipGetLastError());
+  return HE_OK;
+}
+
+// Integer weights w_i = rint(alpha_i * q_{L-1}) (ties to even), validated.
+he_status integer_weights(const he_ctx* ctx, uint32_t K, const double* alpha, bool check_sum, std::vector<uint32_t>* w) {
+  const double q_last = (double)ctx->primes.back();
+  double sum = 0.0;
+  w->resize(K);
+  for (uint32_t i = 0; i < K; ++i) {
+    if (!(alpha[i] > 0.0) || !std::isfinite(alpha[i])) return fail(HE_ERR_INVALID_ARG, "aggregation weight must be positive and finite");
+    const double r = std::nearbyint(alpha[i] * q_last);  // default rounding mode: to nearest, ties to even
+    if (r < 1.0 || r > q_last) return fail(HE_ERR_INVALID_ARG, "aggregation weight rounds to 0 or exceeds 1");
+    (*w)[i] = (uint32_t)r;
+    sum += alpha[i];
+  }
+  if (check_sum && std::fabs(sum - 1.0) > 1e-9) return fail(HE_ERR_INVALID_ARG, "aggregation weights must sum to 1");
+  return HE_OK;
+}
+
+// Folds K clients into (acc_ct, acc_plain) or, when `fin`, writes the final outputs.
+he_status aggregate_impl(he_ctx* ctx, uint32_t K, const double* alpha, const std::vector<uint32_t>& w,
+                         const uint32_t* const* ct_in, const float* const* plain_in, uint64_t n_ct, uint64_t n_plain,
+                         bool has_acc, bool fin, uint32_t* acc_ct, double* acc_plain, uint32_t* ct_out, float* plain_out,
+                         hipStream_t st) {
+  const uint32_t L = ctx->ring.L;
+  uint32_t done = 0;
+  bool acc_live = has_acc;
+  do {
+    const uint32_t kc = std::min<uint32_t>(kAggClients, K - done);
+    const bool last = (done + kc == K);
+    AggArgs a{};
+    PlainArgs pa{};
+    a.K = pa.K = kc;
+    for (uint32_t i = 0; i < kc; ++i) {
+      a.ct[i] = n_ct ? ct_in[done + i] : nullptr;
+      for (uint32_t j = 0; j < L; ++j) a.w[i][j] = w[done + i] % ctx->primes[j];
+      pa.w[i] = n_plain ? plain_in[done + i] : nullptr;
+      pa.alpha[i] = alpha[done + i];
+    }
+    const bool do_fin = fin && last;
+    he_status s = launch_agg(ctx, acc_live, do_fin, a, n_ct, acc_ct, do_fin ? ct_out : acc_ct, st);
+    if (s != HE_OK) return s;
+    s = launch_plain(acc_live, do_fin, pa, n_plain, acc_plain, acc_plain, plain_out, st);
+    if (s != HE_OK) return s;
+    acc_live = true;
+    done += kc;
+  } while (done < K);
+  return HE_OK;
+}
+
+}  // namespace
+
+// =========================================================================================
+// C ABI
+// =========================================================================================
+
+extern "C" {
+
+const char* he_last_error(void) { return g_last_error.c_str(); }
+
+he_status he_ctx_create(const he_params* params, int device, he_ctx** out) {
+  if (!params || !out) return fail(HE_ERR_INVALID_ARG, "params/out is null");
+  *out = nullptr;
+  if (params->log2_n < 3 || params->log2_n > 14) return fail(HE_ERR_INVALID_ARG, "log2_n must be in 3..14");
+  if (params->n_limbs < 2 || params->n_limbs > (uint32_t)kMaxLimbs) return fail(HE_ERR_INVALID_ARG, "n_limbs must be in 2..8");
+  if (params->scale_bits < 1 || params->scale_bits > 30) return fail(HE_ERR_INVALID_ARG, "scale_bits must be in 1..30");
+  if (params->cbd_eta > 32) return fail(HE_ERR_INVALID_ARG, "cbd_eta must be in 0..32");
+  HIP_TRY(hipSetDevice(device));
+  he_ctx* ctx = new (std::nothrow) he_ctx();
+  if (!ctx) return fail(HE_ERR_NOMEM, "host allocation failed");
+  ctx->device = device;
+  const uint32_t logN = params->log2_n, N = 1u << logN, n = N / 2, L = params->n_limbs;
+  if (params->primes) {
+    ctx->primes.assign(params->primes, params->primes + L);
+    for (uint32_t j = 0; j < L; ++j) {
+      const uint32_t q = ctx->primes[j];
+      if (q <= (1u << 30) || q >= (1u << 31) || (q - 1) % (2 * N) != 0 || !he_host::is_prime_u32(q) ||
+          (j > 0 && q >= ctx->primes[j - 1])) {
+        delete ctx;
+        return fail(HE_ERR_INVALID_ARG, "primes must be descending primes in (2^30, 2^31) with q = 1 mod 2N");
+      }
+    }
+  } else if (!he_host::find_primes(logN, L, &ctx->primes) || ctx->primes.back() <= (1u << 30)) {
+    delete ctx;
+    return fail(HE_ERR_INVALID_ARG, "not enough primes below 2^31 for this ring");
+  }
+  RingDev& rg = ctx->ring;
+  rg.logN = logN; rg.N = N; rg.L = L; rg.scale_bits = params->scale_bits; rg.eta = params->cbd_eta;
+
+  std::vector<uint2> twf((size_t)L * N), twi((size_t)L * N);
+  static_assert(sizeof(he_host::U2) == sizeof(uint2), "layout");
+  for (uint32_t j = 0; j < L; ++j) {
+    const uint32_t q = ctx->primes[j];
+    const uint32_t psi = he_host::smallest_primitive_2n_root(q, logN);
+    he_host::power_table_bitrev(q, psi, logN, reinterpret_cast<he_host::U2*>(twf.data() + (size_t)j * N));
+    he_host::power_table_bitrev(q, he_host::invmod(psi, q), logN, reinterpret_cast<he_host::U2*>(twi.data() + (size_t)j * N));
+    rg.q[j] = q;
+    const he_host::U2 ni = he_host::shoup(he_host::invmod(N % q, q), q);
+    rg.ninv[j] = make_uint2(ni.w, ni.wp);
+    const uint32_t q_last = ctx->primes[L - 1];
+    ctx->agg.q[j] = q;
+    const he_host::U2 c32 = he_host::shoup((uint32_t)((1ull << 32) % q), q);
+    ctx->agg.c32[j] = make_uint2(c32.w, c32.wp);
+    if (j + 1 < L) {
+      const he_host::U2 qi = he_host::shoup(he_host::invmod(q_last % q, q), q);
+      ctx->agg.qlinv[j] = make_uint2(qi.w, qi.wp);
+      ctx->agg.qdiff[j] = q - q_last;
+    }
+  }
+  ctx->agg.half_last = (ctx->primes[L - 1] - 1) / 2;
+
+  std::vector<uint2> garner((size_t)kMaxLimbs * kMaxLimbs, make_uint2(0, 0));
+  for (uint32_t i = 0; i < L; ++i)
+    for (uint32_t j = i + 1; j < L; ++j) {
+      const he_host::U2 v = he_host::shoup(he_host::invmod(ctx->primes[i] % ctx->primes[j], ctx->primes[j]), ctx->primes[j]);
+      garner[i * kMaxLimbs + j] = make_uint2(v.w, v.wp);
+    }
+
+  std::vector<double2> fe(std::max<uint32_t>(1, n / 2)), tws(n);
+  for (uint32_t r = 0; r < n / 2; ++r) {
+    const he_host::D2 v = he_host::unit_root(r, n);
+    fe[r] = make_double2(v.x, -v.y);
+  }
+  for (uint32_t k = 0; k < n; ++k) {
+    const he_host::D2 v = he_host::unit_root(k, 4ull * n);
+    tws[k] = make_double2(v.x, v.y);
+  }
+  std::vector<uint32_t> bins, penc(n), pdec(n);
+  he_host::slot_bins(logN, &bins);
+  for (uint32_t j = 0; j < n; ++j) {
+    pdec[j] = bins[j];
+    penc[j] = he_host::bitrev(bins[j], (int)logN - 1);
+  }
+
+  he_status s = HE_OK;
+  if (s == HE_OK) s = upload(ctx, twf, &rg.tw_fwd);
+  if (s == HE_OK) s = upload(ctx, twi, &rg.tw_inv);
+  if (s == HE_OK) s = upload(ctx, fe, &rg.fft_e);
+  if (s == HE_OK) s = upload(ctx, tws, &rg.twist);
+  if (s == HE_OK) s = upload(ctx, penc, &rg.perm_enc);
+  if (s == HE_OK) s = upload(ctx, pdec, &rg.perm_dec);
+  if (s == HE_OK) s = upload(ctx, garner, &rg.garner_inv);
+  // kernels that need more than the default dynamic LDS
+  if (s == HE_OK) s = allow_lds(k_encode, fft_lds_bytes(n));
+  if (s == HE_OK) s = allow_lds(k_encrypt, ntt_lds_bytes(N, 2));
+  if (s == HE_OK) s = allow_lds(k_decrypt, ntt_lds_bytes(N, 1));
+  if (s == HE_OK) s = allow_lds(k_ntt_batch<false>, ntt_lds_bytes(N, 1));
+  if (s == HE_OK) s = allow_lds(k_ntt_batch<true>, ntt_lds_bytes(N, 1));
+  if (s == HE_OK) s = allow_lds(k_decode<1>, fft_lds_bytes(n));
+  if (s == HE_OK) s = allow_lds(k_decode<2>, fft_lds_bytes(n));
+  if (s == HE_OK) s = allow_lds(k_decode<3>, fft_lds_bytes(n));
+  if (s == HE_OK) s = allow_lds(k_decode<4>, fft_lds_bytes(n));
+  if (s == HE_OK) s = allow_lds(k_decode<5>, fft_lds_bytes(n));
+  if (s == HE_OK) s = allow_lds(k_decode<6>, fft_lds_bytes(n));
+  if (s == HE_OK) s = allow_lds(k_decode<7>, fft_lds_bytes(n));
+  if (s == HE_OK) s = allow_lds(k_decode<8>, fft_lds_bytes(n));
+  if (s != HE_OK) {
+    he_ctx_destroy(ctx);
+    return s;
+  }
+  *out = ctx;
+  return HE_OK;
+}
+
+void he_ctx_destroy(he_ctx* ctx) {
+  if (!ctx) return;
+  (void)hipSetDevice(ctx->device);
+  (void)hipDeviceSynchronize();
+  for (void* p : ctx->dev_allocs) (void)hipFree(p);
+  if (ctx->ws) (void)hipFree(ctx->ws);
+  delete ctx;
+}
+
+he_status he_ctx_primes(const he_ctx* ctx, uint32_t* primes_host) {
+  if (!ctx || !primes_host) return fail(HE_ERR_INVALID_ARG, "null argument");
+  std::copy(ctx->primes.begin(), ctx->primes.end(), primes_host);
+  return HE_OK;
+}
+
+uint32_t he_ctx_ring_degree(const he_ctx* ctx) { return ctx ? ctx->ring.N : 0; }
+uint32_t he_ctx_n_limbs(const he_ctx* ctx) { return ctx ? ctx->ring.L : 0; }
+uint64_t he_ct_bytes(const he_ctx* ctx, uint32_t level) { return ctx ? 2ull * level * ctx->ring.N * 4ull : 0; }
+
+// ---- keys ------------------------------------------------------------------------------
+
+he_status he_keygen(he_ctx* ctx, uint64_t seed, he_pk** pk_out, he_sk** sk_out, void* stream) {
+  he_status s = check_ctx(ctx);
+  if (s != HE_OK) return s;
+  if (!pk_out || !sk_out) return fail(HE_ERR_INVALID_ARG, "pk/sk out pointer is null");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const RingDev& rg = ctx->ring;
+  const size_t LN = (size_t)rg.L * rg.N;
+  he_pk* pk = new (std::nothrow) he_pk{ctx, nullptr, nullptr};
+  he_sk* sk = new (std::nothrow) he_sk{ctx, nullptr, nullptr};
+  if (!pk || !sk) {
+    delete pk;
+    delete sk;
+    return fail(HE_ERR_NOMEM, "host allocation failed");
+  }
+  uint32_t* tmp = nullptr;  // s_res, e_res, a_res: 3 x [L][N]
+  auto cleanup = [&]() {
+    if (tmp) (void)hipFree(tmp);
+    he_pk_destroy(pk);
+    he_sk_destroy(sk);
+  };
+#define KG_TRY(expr)                      \
+  do {                                    \
+    hipError_t e_ = (expr);               \
+    if (e_ != hipSuccess) {               \
+      cleanup();                          \
+      return fail(HE_ERR_HIP, std::string(#expr) + ": " + hipGetErrorString(e_)); \
+    }                                     \
+  } while (0)
+  KG_TRY(hipMalloc(&pk->tab, 2 * LN * sizeof(uint2)));
+  KG_TRY(hipMalloc(&pk->raw, 2 * LN * sizeof(uint32_t)));
+  KG_TRY(hipMalloc(&sk->tab, LN * sizeof(uint2)));
+  KG_TRY(hipMalloc(&sk->coeff, std::max<size_t>(rg.N, 16)));
+  KG_TRY(hipMalloc(&tmp, 3 * LN * sizeof(uint32_t)));
+  uint32_t *s_res = tmp, *e_res = tmp + LN, *a_res = tmp + 2 * LN;
+  const uint2 key = make_uint2((uint32_t)seed, (uint32_t)(seed >> 32));
+  const dim3 g1((rg.N + 255) / 256), b1(256);
+  hipLaunchKernelGGL(k_keygen_sample, g1, b1, 0, st, rg, key, sk->coeff, s_res, e_res, a_res);
+  KG_TRY(hipGetLastError());
+  // forward transform of all 3L polynomials: polynomial index b -> limb b % L
+  hipLaunchKernelGGL(k_ntt_batch<false>, dim3(3 * rg.L), dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 1), st, rg, -1, tmp);
+  KG_TRY(hipGetLastError());
+  hipLaunchKernelGGL(k_keygen_combine, g1, b1, 0, st, rg, s_res, e_res, a_res, pk->raw, pk->tab, sk->tab);
+  KG_TRY(hipGetLastError());
+  KG_TRY(hipStreamSynchronize(st));  // tmp is freed below
+  KG_TRY(hipFree(tmp));
+  tmp = nullptr;
+#undef KG_TRY
+  *pk_out = pk;
+  *sk_out = sk;
+  return HE_OK;
+}
+
+void he_pk_destroy(he_pk* pk) {
+  if (!pk) return;
+  if (pk->tab) (void)hipFree(pk->tab);
+  if (pk->raw) (void)hipFree(pk->raw);
+  delete pk;
+}
+
+void he_sk_destroy(he_sk* sk) {
+  if (!sk) return;
+  if (sk->tab) (void)hipFree(sk->tab);
+  if (sk->coeff) (void)hipFree(sk->coeff);
+  delete sk;
+}
+
+// ---- mask ------------------------------------------------------------------------------
+
+he_status he_mask_create(he_ctx* ctx, uint64_t P, const uint64_t* starts, const uint64_t* lens, uint64_t n_runs,
+                         he_mask** out) {
+  he_status s = check_ctx(ctx);
+  if (s != HE_OK) return s;
+  if (!out || (n_runs && (!starts || !lens))) return fail(HE_ERR_INVALID_ARG, "null argument");
+  if (n_runs >= (1ull << 31)) return fail(HE_ERR_INVALID_ARG, "too many runs");
+  // validate and build prefix sums + complement runs on the host
+  std::vector<uint64_t> block;  // start | prefix | cstart | cprefix
+  std::vector<uint64_t> st_v, pf_v, cs_v, cp_v;
+  uint64_t pos = 0, packed = 0, cpacked = 0;
+  for (uint64_t r = 0; r < n_runs; ++r) {
+    if (lens[r] == 0 || starts[r] < pos || starts[r] > P || lens[r] > P - starts[r])
+      return fail(HE_ERR_INVALID_ARG, "mask runs must be sorted, disjoint, non-empty and inside [0, P)");
+    if (starts[r] > pos) {
+      cs_v.push_back(pos);
+      cp_v.push_back(cpacked);
+      cpacked += starts[r] - pos;
+    }
+    st_v.push_back(starts[r]);
+    pf_v.push_back(packed);
+    packed += lens[r];
+    pos = starts[r] + lens[r];
+  }
+  if (pos < P) {
+    cs_v.push_back(pos);
+    cp_v.push_back(cpacked);
+    cpacked += P - pos;
+  }
+  pf_v.push_back(packed);
+  cp_v.push_back(cpacked);
+  he_mask* mk = new (std::nothrow) he_mask();
+  if (!mk) return fail(HE_ERR_NOMEM, "host allocation failed");
+  mk->ctx = ctx;
+  const size_t o_st = 0, o_pf = o_st + st_v.size() + 1, o_cs = o_pf + pf_v.size(), o_cp = o_cs + cs_v.size() + 1;
+  block.assign(o_cp + cp_v.size(), 0);
+  std::copy(st_v.begin(), st_v.end(), block.begin() + o_st);
+  std::copy(pf_v.begin(), pf_v.end(), block.begin() + o_pf);
+  std::copy(cs_v.begin(), cs_v.end(), block.begin() + o_cs);
+  std::copy(cp_v.begin(), cp_v.end(), block.begin() + o_cp);
+  hipError_t e = hipMalloc(&mk->dev_block, block.size() * sizeof(uint64_t));
+  if (e == hipSuccess) e = hipMemcpy(mk->dev_block, block.data(), block.size() * sizeof(uint64_t), hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    he_mask_destroy(mk);
+    return fail(HE_ERR_HIP, std::string("mask upload: ") + hipGetErrorString(e));
+  }
+  const uint64_t* base = static_cast<const uint64_t*>(mk->dev_block);
+  mk->dev.start = base + o_st;
+  mk->dev.prefix = base + o_pf;
+  mk->dev.cstart = base + o_cs;
+  mk->dev.cprefix = base + o_cp;
+  mk->dev.n_runs = (uint32_t)st_v.size();
+  mk->dev.n_cruns = (uint32_t)cs_v.size();
+  mk->dev.P = P;
+  mk->dev.P_enc = packed;
+  *out = mk;
+  return HE_OK;
+}
+
+he_status he_mask_from_bytes(he_ctx* ctx, uint64_t P, const uint8_t* mask_dev, he_mask** out, void* stream) {
+  he_status s = check_ctx(ctx);
+  if (s != HE_OK) return s;
+  if (!out || (P && !mask_dev)) return fail(HE_ERR_INVALID_ARG, "null argument");
+  std::vector<uint8_t> host(P);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (P) {
+    HIP_TRY(hipMemcpyAsync(host.data(), mask_dev, P, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+  }
+  std::vector<uint64_t> starts, lens;
+  uint64_t i = 0;
+  while (i < P) {
+    if (!host[i]) {
+      ++i;
+      continue;
+    }
+    uint64_t b = i;
+    while (i < P && host[i]) ++i;
+    starts.push_back(b);
+    lens.push_back(i - b);
+  }
+  return he_mask_create(ctx, P, starts.data(), lens.data(), starts.size(), out);
+}
+
+void he_mask_destroy(he_mask* mask) {
+  if (!mask) return;
+  if (mask->dev_block) (void)hipFree(mask->dev_block);
+  delete mask;
+}
+
+uint64_t he_mask_n_params(const he_mask* mask) { return mask ? mask->dev.P : 0; }
+uint64_t he_mask_n_enc(const he_mask* mask) { return mask ? mask->dev.P_enc : 0; }
+uint64_t he_n_ct(const he_ctx* ctx, const he_mask* mask) {
+  if (!ctx || !mask) return 0;
+  const uint64_t n = ctx->ring.N / 2;
+  return (mask->dev.P_enc + n - 1) / n;
+}
+
+// ---- client: encrypt -------------------------------------------------------------------
+
+he_status he_encrypt_masked(he_ctx* ctx, const he_pk* pk, const he_mask* mask, uint64_t seed, uint32_t client_id,
+                            const float* w_dev, uint32_t* ct_out_dev, float* plain_out_dev, void* stream) {
+  he_status s = check_ctx(ctx);
+  if (s != HE_OK) return s;
+  if (!pk || !mask || pk->ctx != ctx || mask->ctx != ctx) return fail(HE_ERR_INVALID_ARG, "key/mask missing or from another context");
+  const MaskDev& mk = mask->dev;
+  const uint64_t n_ct = he_n_ct(ctx, mask), n_plain = mk.P - mk.P_enc;
+  if ((mk.P && !w_dev) || (n_ct && !ct_out_dev) || (n_plain && !plain_out_dev)) return fail(HE_ERR_INVALID_ARG, "null data pointer");
+  if (n_ct >= (1ull << 32)) return fail(HE_ERR_INVALID_ARG, "too many ciphertexts");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const RingDev& rg = ctx->ring;
+  const uint64_t chunk = std::min<uint64_t>(kCtChunk, n_ct);
+  const size_t N = rg.N;
+  if (chunk) {
+    s = ensure_ws(ctx, chunk * N * 6);  // int32 me0 + int8 u + int8 e1
+    if (s != HE_OK) return s;
+  }
+  int32_t* me0 = static_cast<int32_t*>(ctx->ws);
+  int8_t* u = reinterpret_cast<int8_t*>(me0 + chunk * N);
+  int8_t* e1 = u + chunk * N;
+  for (uint64_t c0 = 0; c0 < n_ct; c0 += chunk) {
+    const uint64_t cn = std::min<uint64_t>(chunk, n_ct - c0);
+    s = launch_encode(ctx, mk, w_dev, nullptr, c0, cn, me0, st);
+    if (s != HE_OK) return s;
+    s = launch_sample_encrypt(ctx, pk, seed, client_id, c0, cn, me0, me0, u, e1, ct_out_dev + c0 * 2 * rg.L * N, st);
+    if (s != HE_OK) return s;
+  }
+  if (n_plain) {
+    hipLaunchKernelGGL(k_plain_move<false>, dim3(grid_for(n_plain, 256, 1u << 16)), dim3(256), 0, st, mk, w_dev, plain_out_dev);
+    HIP_TRY(hipGetLastError());
+  }
+  return HE_OK;
+}
+
+// ---- server: aggregate -----------------------------------------------------------------
+
+he_status he_aggregate(he_ctx* ctx, uint32_t K, const double* alpha_host, const uint32_t* const* ct_in_dev,
+                       const float* const* plain_in_dev, uint64_t n_ct, uint64_t n_plain, uint32_t* ct_out_dev,
+                       float* plain_out_dev, void* stream) {
+  he_status s = check_ctx(ctx);
+  if (s != HE_OK) return s;
+  if (K == 0 || K > HE_MAX_CLIENTS_PER_CALL) return fail(HE_ERR_INVALID_ARG, "K must be in 1..HE_MAX_CLIENTS_PER_CALL");
+  if (!alpha_host || (n_ct && (!ct_in_dev || !ct_out_dev)) || (n_plain && (!plain_in_dev || !plain_out_dev)))
+    return fail(HE_ERR_INVALID_ARG, "null argument");
+  for (uint32_t i = 0; i < K; ++i)
+    if ((n_ct && !ct_in_dev[i]) || (n_plain && !plain_in_dev[i])) return fail(HE_ERR_INVALID_ARG, "null client buffer");
+  std::vector<uint32_t> w;
+  s = integer_weights(ctx, K, alpha_host, true, &w);
+  if (s != HE_OK) return s;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  uint32_t* acc_ct = nullptr;
+  double* acc_plain = nullptr;
+  if (K > (uint32_t)kAggClients) {  // more clients than one launch folds: internal accumulators
+    const size_t ct_bytes = (size_t)n_ct * 2 * ctx->ring.L * ctx->ring.N * 4;
+    const size_t ct_bytes_al = (ct_bytes + 255) & ~(size_t)255;
+    s = ensure_ws(ctx, ct_bytes_al + n_plain * sizeof(double));
+    if (s != HE_OK) return s;
+    acc_ct = static_cast<uint32_t*>(ctx->ws);
+    acc_plain = reinterpret_cast<double*>(static_cast<char*>(ctx->ws) + ct_bytes_al);
+  }
+  return aggregate_impl(ctx, K, alpha_host, w, ct_in_dev, plain_in_dev, n_ct, n_plain, false, true, acc_ct, acc_plain,
+                        ct_out_dev, plain_out_dev, st);
+}
+
+he_status he_aggregate_begin(he_ctx* ctx, uint64_t n_ct, uint64_t n_plain, uint32_t* acc_ct_dev, double* acc_plain_dev,
+                             void* stream) {
+  he_status s = check_ctx(ctx);
+  if (s != HE_OK) return s;
+  if ((n_ct && !acc_ct_dev) || (n_plain && !acc_plain_dev)) return fail(HE_ERR_INVALID_ARG, "null accumulator");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const uint64_t n_words = n_ct * 2 * ctx->ring.L * ctx->ring.N;
+  if (n_words) {
+    hipLaunchKernelGGL(k_fill_u32, dim3(grid_for(n_words, 256, 1u << 16)), dim3(256), 0, st, acc_ct_dev, n_words, 0u);
+    HIP_TRY(hipGetLastError());
+  }
+  if (n_plain) {
+    hipLaunchKernelGGL(k_fill_u32, dim3(grid_for(n_plain * 2, 256, 1u << 16)), dim3(256), 0, st,
+                       reinterpret_cast<uint32_t*>(acc_plain_dev), n_plain * 2, 0u);
+    HIP_TRY(hipGetLastError());
+  }
+  return HE_OK;
+}
+
+he_status he_aggregate_add(he_ctx* ctx, uint32_t K_chunk, const double* alpha_host, const uint32_t* const* ct_in_dev,
+                           const float* const* plain_in_dev, uint64_t n_ct, uint64_t n_plain, uint32_t* acc_ct_dev,
+                           double* acc_plain_dev, void* stream) {
+  he_status s = check_ctx(ctx);
+  if (s != HE_OK) return s;
+  if (K_chunk == 0 || K_chunk > HE_MAX_CLIENTS_PER_CALL) return fail(HE_ERR_INVALID_ARG, "K_chunk must be in 1..HE_MAX_CLIENTS_PER_CALL");
+  if (!alpha_host || (n_ct && (!ct_in_dev || !acc_ct_dev)) || (n_plain && (!plain_in_dev || !acc_plain_dev)))
+    return fail(HE_ERR_INVALID_ARG, "null argument");
+  for (uint32_t i = 0; i < K_chunk; ++i)
+    if ((n_ct && !ct_in_dev[i]) || (n_plain && !plain_in_dev[i])) return fail(HE_ERR_INVALID_ARG, "null client buffer");
+  std::vector<uint32_t> w;
+  s = integer_weights(ctx, K_chunk, alpha_host, false, &w);
+  if (s != HE_OK) return s;
+  return aggregate_impl(ctx, K_chunk, alpha_host, w, ct_in_dev, plain_in_dev, n_ct, n_plain, true, false, acc_ct_dev,
+                        acc_plain_dev, nullptr, nullptr, static_cast<hipStream_t>(stream));
+}
+
+he_status he_aggregate_finalize(he_ctx* ctx, uint64_t n_ct, uint64_t n_plain, const uint32_t* acc_ct_dev,
+                                const double* acc_plain_dev, uint32_t* ct_out_dev, float* plain_out_dev, void* stream) {
+  he_status s = check_ctx(ctx);
+  if (s != HE_OK) return s;
+  if ((n_ct && (!acc_ct_dev || !ct_out_dev)) || (n_plain && (!acc_plain_dev || !plain_out_dev)))
+    return fail(HE_ERR_INVALID_ARG, "null argument");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  AggArgs a{};
+  PlainArgs pa{};
+  s = launch_agg(ctx, true, true, a, n_ct, acc_ct_dev, ct_out_dev, st);
+  if (s != HE_OK) return s;
+  return launch_plain(true, true, pa, n_plain, acc_plain_dev, nullptr, plain_out_dev, st);
+}
+
+// ---- client: decrypt + merge -----------------------------------------------------------
+
+he_status he_decrypt_merge(he_ctx* ctx, const he_sk* sk, const he_mask* mask, const uint32_t* ct_glob_dev,
+                           const float* plain_glob_dev, float* w_out_dev, void* stream) {
+  he_status s = check_ctx(ctx);
+  if (s != HE_OK) return s;
+  if (!sk || !mask || sk->ctx != ctx || mask->ctx != ctx) return fail(HE_ERR_INVALID_ARG, "key/mask missing or from another context");
+  const MaskDev& mk = mask->dev;
+  const uint64_t n_ct = he_n_ct(ctx, mask), n_plain = mk.P - mk.P_enc;
+  if ((mk.P && !w_out_dev) || (n_ct && !ct_glob_dev) || (n_plain && !plain_glob_dev)) return fail(HE_ERR_INVALID_ARG, "null data pointer");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const RingDev& rg = ctx->ring;
+  const uint32_t level = rg.L - 1;
+  const uint64_t chunk = std::min<uint64_t>(kCtChunk, n_ct);
+  const size_t N = rg.N;
+  if (chunk) {
+    s = ensure_ws(ctx, chunk * level * N * 4);
+    if (s != HE_OK) return s;
+  }
+  uint32_t* d = static_cast<uint32_t*>(ctx->ws);
+  for (uint64_t c0 = 0; c0 < n_ct; c0 += chunk) {
+    const uint64_t cn = std::min<uint64_t>(chunk, n_ct - c0);
+    s = launch_decrypt(ctx, sk, ct_glob_dev + c0 * 2 * level * N, cn, level, d, st);
+    if (s != HE_OK) return s;
+    s = launch_decode(ctx, level, mk, d, c0, cn, w_out_dev, nullptr, st);
+    if (s != HE_OK) return s;
+  }
+  if (n_plain) {
+    hipLaunchKernelGGL(k_plain_move<true>, dim3(grid_for(n_plain, 256, 1u << 16)), dim3(256), 0, st, mk, plain_glob_dev, w_out_dev);
+    HIP_TRY(hipGetLastError());
+  }
+  return HE_OK;
+}
+
+// ---- test / measurement exports ---------------------------------------------------------
+
+he_status he_debug_encode(he_ctx* ctx, const float* slots_dev, uint64_t n_ct, int32_t* m_out_dev, void* stream) {
+  he_status s = check_ctx(ctx);
+  if (s != HE_OK) return s;
+  if (n_ct == 0) return HE_OK;
+  if (!slots_dev || !m_out_dev) return fail(HE_ERR_INVALID_ARG, "null argument");
+  if (n_ct >= (1ull << 31)) return fail(HE_ERR_INVALID_ARG, "too many ciphertexts");
+  MaskDev mk{};
+  return launch_encode(ctx, mk, nullptr, slots_dev, 0, n_ct, m_out_dev, static_cast<hipStream_t>(stream));
+}
+
+he_status he_debug_encrypt_plain(he_ctx* ctx, const he_pk* pk, uint64_t seed, uint32_t client_id, uint64_t first_ct,
+                                 const int32_t* m_dev, uint64_t n_ct, uint32_t* ct_out_dev, void* stream) {
+  he_status s = check_ctx(ctx);
+  if (s != HE_OK) return s;
+  if (n_ct == 0) return HE_OK;
+  if (!pk || pk->ctx != ctx || !m_dev || !ct_out_dev) return fail(HE_ERR_INVALID_ARG, "null argument or key from another context");
+  if (first_ct + n_ct > (1ull << 32)) return fail(HE_ERR_INVALID_ARG, "ciphertext index out of range");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const RingDev& rg = ctx->ring;
+  const size_t N = rg.N;
+  const uint64_t chunk = std::min<uint64_t>(kCtChunk, n_ct);
+  s = ensure_ws(ctx, chunk * N * 6);
+  if (s != HE_OK) return s;
+  int32_t* me0 = static_cast<int32_t*>(ctx->ws);
+  int8_t* u = reinterpret_cast<int8_t*>(me0 + chunk * N);
+  int8_t* e1 = u + chunk * N;
+  for (uint64_t c0 = 0; c0 < n_ct; c0 += chunk) {
+    const uint64_t cn = std::min<uint64_t>(chunk, n_ct - c0);
+    s = launch_sample_encrypt(ctx, pk, seed, client_id, first_ct + c0, cn, m_dev + c0 * N, me0, u, e1,
+                              ct_out_dev + c0 * 2 * rg.L * N, st);
+    if (s != HE_OK) return s;
+  }
+  return HE_OK;
+}
+
+he_status he_debug_decrypt_residues(he_ctx* ctx, const he_sk* sk, const uint32_t* ct_dev, uint64_t n_ct, uint32_t level,
+                                    uint32_t* d_out_dev, void* stream) {
+  he_status s = check_ctx(ctx);
+  if (s != HE_OK) return s;
+  if (n_ct == 0) return HE_OK;
+  if (!sk || sk->ctx != ctx || !ct_dev || !d_out_dev) return fail(HE_ERR_INVALID_ARG, "null argument or key from another context");
+  if (level < 1 || level > ctx->ring.L) return fail(HE_ERR_LEVEL, "level must be in 1..L");
+  if (n_ct >= 65536) {  // grid y limit: go chunk by chunk
+    const size_t N = ctx->ring.N;
+    for (uint64_t c0 = 0; c0 < n_ct; c0 += 32768) {
+      const uint64_t cn = std::min<uint64_t>(32768, n_ct - c0);
+      s = launch_decrypt(ctx, sk, ct_dev + c0 * 2 * level * N, cn, level, d_out_dev + c0 * level * N, static_cast<hipStream_t>(stream));
+      if (s != HE_OK) return s;
+    }
+    return HE_OK;
+  }
+  return launch_decrypt(ctx, sk, ct_dev, n_ct, level, d_out_dev, static_cast<hipStream_t>(stream));
+}
+
+he_status he_debug_decode(he_ctx* ctx, const uint32_t* d_dev, uint64_t n_ct, uint32_t level, double* slots_out_dev,
+                          void* stream) {
+  he_status s = check_ctx(ctx);
+  if (s != HE_OK) return s;
+  if (n_ct == 0) return HE_OK;
+  if (!d_dev || !slots_out_dev) return fail(HE_ERR_INVALID_ARG, "null argument");
+  if (level < 1 || level > ctx->ring.L) return fail(HE_ERR_LEVEL, "level must be in 1..L");
+  if (n_ct >= (1ull << 31)) return fail(HE_ERR_INVALID_ARG, "too many ciphertexts");
+  MaskDev mk{};
+  return launch_decode(ctx, level, mk, d_dev, 0, n_ct, nullptr, slots_out_dev, static_cast<hipStream_t>(stream));
+}
+
+he_status he_debug_ntt(he_ctx* ctx, int inverse, uint32_t limb, uint32_t* polys_dev, uint64_t batch, void* stream) {
+  he_status s = check_ctx(ctx);
+  if (s != HE_OK) return s;
+  if (batch == 0) return HE_OK;
+  if (!polys_dev) return fail(HE_ERR_INVALID_ARG, "null argument");
+  if (limb >= ctx->ring.L) return fail(HE_ERR_INVALID_ARG, "limb out of range");
+  if (batch >= (1ull << 31)) return fail(HE_ERR_INVALID_ARG, "batch too large");
+  const RingDev& rg = ctx->ring;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (inverse)
+    hipLaunchKernelGGL(k_ntt_batch<true>, dim3((uint32_t)batch), dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 1), st, rg, (int)limb, polys_dev);
+  else
+    hipLaunchKernelGGL(k_ntt_batch<false>, dim3((uint32_t)batch), dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 1), st, rg, (int)limb, polys_dev);
+  HIP_TRY(hipGetLastError());
+  return HE_OK;
+}
+
+he_status he_debug_export_keys(he_ctx* ctx, const he_pk* pk, const he_sk* sk, uint32_t* pk_coeff_dev, int32_t* sk_coeff_dev,
+                               void* stream) {
+  he_status s = check_ctx(ctx);
+  if (s != HE_OK) return s;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const RingDev& rg = ctx->ring;
+  if (pk_coeff_dev) {
+    if (!pk || pk->ctx != ctx) return fail(HE_ERR_INVALID_ARG, "public key missing or from another context");
+    HIP_TRY(hipMemcpyAsync(pk_coeff_dev, pk->raw, 2ull * rg.L * rg.N * 4, hipMemcpyDeviceToDevice, st));
+    hipLaunchKernelGGL(k_ntt_batch<true>, dim3(2 * rg.L), dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 1), st, rg, -1, pk_coeff_dev);
+    HIP_TRY(hipGetLastError());
+  }
+  if (sk_coeff_dev) {
+    if (!sk || sk->ctx != ctx) return fail(HE_ERR_INVALID_ARG, "secret key missing or from another context");
+    hipLaunchKernelGGL(k_widen_i8, dim3((rg.N + 255) / 256), dim3(256), 0, st, sk->coeff, sk_coeff_dev, rg.N);
+    HIP_TRY(hipGetLastError());
+  }
+  return HE_OK;
+}
+
+}  // extern "C"

@@ -1,4 +1,4 @@
-"""Seeded synthetic workloads shared by the GPU tests, the benchmark and the CPU oracle's tests.
+"""Seeded synthetic workloads shared by the GPU tests, the benchmark and the CPU reference checks.
 
 Holds no arithmetic of the method: only the shapes, value distributions and
 mask structure of the five workloads (model-sized Gaussian parameter vectors,

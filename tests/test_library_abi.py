@@ -1,0 +1,48 @@
+"""Host-only checks: the C-ABI library loads and exports every symbol the header declares."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "he_fedavg.h")
+
+
+def _lib_path():
+    from paper_2303_10837_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build_library()
+    return binding.LIB_PATH
+
+
+def test_header_symbols_are_exported_and_bound():
+    from paper_2303_10837_amd import binding
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    declared = set(re.findall(r"\b(he_[a-z0-9_]+)\s*\(", text))
+    assert {"he_keygen", "he_encrypt_masked", "he_aggregate", "he_decrypt_merge"} <= declared
+    lib = ctypes.CDLL(_lib_path())
+    for name in declared:
+        assert hasattr(lib, name), f"{name} declared in the header but not exported"
+    assert declared == set(binding.EXPORTED_SYMBOLS)
+
+
+def test_no_cpu_fallback_when_library_is_missing(monkeypatch, tmp_path):
+    from paper_2303_10837_amd import binding
+    monkeypatch.setattr(binding, "_LIB", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(RuntimeError):
+        binding.load()
+
+
+def test_product_never_imports_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2303_10837_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle", src, flags=re.M), f"{f} imports the oracle"
+    for dirpath, _, files in os.walk(os.path.join(ROOT, "oracle")):
+        for f in files:
+            if f.endswith(".py"):
+                assert "paper_2303_10837_amd" not in open(os.path.join(dirpath, f)).read()
