@@ -166,8 +166,9 @@ he_status he_decrypt_merge(he_ctx* ctx, const he_sk* sk, const he_mask* mask,
    m_k = rint((2*Delta/N) * sum_j z_j cos(pi * 5^j * k / N)). */
 he_status he_debug_encode(he_ctx* ctx, const float* slots_dev, uint64_t n_ct, int32_t* m_out_dev,
                           void* stream);
-/* Encryption of given integer plaintexts m_dev int32[n_ct][N] (ciphertext indices
-   first_ct .. first_ct + n_ct - 1 of client `client_id`) -> ct_out_dev uint32[n_ct][2][L][N]. */
+/* Encryption of given integer plaintexts m_dev int32[n_ct][N], |m| <= 2^31 - 33 so that
+   m + e0 fits 32 bits (ciphertext indices first_ct .. first_ct + n_ct - 1 of client
+   `client_id`) -> ct_out_dev uint32[n_ct][2][L][N]. */
 he_status he_debug_encrypt_plain(he_ctx* ctx, const he_pk* pk, uint64_t seed, uint32_t client_id,
                                  uint64_t first_ct, const int32_t* m_dev, uint64_t n_ct,
                                  uint32_t* ct_out_dev, void* stream);

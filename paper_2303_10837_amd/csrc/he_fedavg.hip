@@ -385,10 +385,16 @@ template <bool HAS_ACC, bool FINAL>
 __global__ void __launch_bounds__(256)
 k_plain_fedavg(PlainArgs a, uint64_t n_plain, const double* __restrict__ acc_in, double* __restrict__ acc_out,
                float* __restrict__ out) {
+  // The product and the sum must round separately (no fused multiply-add), or the result
+  // depends on the compiler's contraction choices.
+#pragma clang fp contract(off)
   const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
   for (uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; t < n_plain; t += stride) {
     double acc = HAS_ACC ? acc_in[t] : 0.0;
-    for (uint32_t i = 0; i < a.K; ++i) acc = __dadd_rn(acc, __dmul_rn(a.alpha[i], (double)a.w[i][t]));
+    for (uint32_t i = 0; i < a.K; ++i) {
+      const double prod = a.alpha[i] * (double)a.w[i][t];
+      acc = acc + prod;
+    }
     if (FINAL) out[t] = (float)acc;
     else acc_out[t] = acc;
   }

@@ -105,7 +105,7 @@ def test_encrypt_given_plaintext(he, log2_n, limbs, eta):
     rs = np.random.default_rng(2)
     n_ct, first, client = 3, 7, 5
     m = rs.integers(-(1 << 29), 1 << 29, (n_ct, p.N)).astype(np.int32)
-    m[1, :8] = [2 ** 31 - 1, -2 ** 31, 0, -1, 1, 2 ** 30, -2 ** 30, 12345]   # extreme plaintext values
+    m[1, :8] = [2 ** 31 - 33, -(2 ** 31 - 33), 0, -1, 1, 2 ** 30, -2 ** 30, 12345]   # extreme plaintext values (m + e0 must fit int32)
     ct = _np(he.he_debug_encrypt_plain(ctx, keys, SEED + 1, client, first, _dev(m))).astype(np.int64)
     for c in range(n_ct):
         ref = osch.encrypt(p, okeys, m[c].astype(np.int64), SEED + 1, client, first + c)
@@ -116,7 +116,7 @@ def test_encrypt_given_plaintext(he, log2_n, limbs, eta):
 def test_aggregate_and_streaming(he, log2_n, limbs, K):
     ctx, _, p, _ = _setup(he, log2_n, limbs)
     rs = np.random.default_rng(3)
-    n_ct, n_plain = 3, 1001
+    n_ct, n_plain = 3, 100_003
     counts = rs.integers(100, 1001, K)
     alpha = counts / counts.sum()
     cts = [np.stack([rs.integers(0, q, (n_ct, 2, p.N)) for q in p.primes], axis=2).astype(np.int64) for _ in range(K)]
