@@ -1,0 +1,177 @@
+#!/usr/bin/env python3
+"""Benchmark of the HE secure-aggregation hot path on one MI355X.
+
+One step = one whole federated round of the workload on one GPU: every client's
+he_encrypt_masked, then he_aggregate, then he_decrypt_merge (inputs resident in HBM).
+Prints ONE JSON line; `value` = K * P_enc / step time (client parameters carried through
+encrypt -> aggregate -> decrypt per second); per-phase rates are in `phases`.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet18_full]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+
+HBM_PEAK_GBS = 8000.0
+# 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: 32-bit integer add / min / mul_lo / mul_hi all issue
+# at one wave64 instruction per 4 cycles per SIMD on gfx950 (measured), so this is the peak
+# for the integer butterfly instruction mix.
+ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+OPS_BUTTERFLY = 12   # Shoup product (mul_hi, 2 mul_lo, sub) + 2 (its reduction) + 3 (mod add) + 3 (mod sub)
+OPS_POINTWISE = 6    # Shoup product + reduction
+OPS_FINAL_ADD = 3
+
+
+def encrypt_ops_per_ct(N, L):
+    log_n = N.bit_length() - 1
+    return L * (3 * (N // 2) * log_n * OPS_BUTTERFLY + 2 * N * OPS_POINTWISE + 2 * N * OPS_FINAL_ADD)
+
+
+def cpu_baseline(w, ws_host, alpha, runs, budget_s=15.0):
+    """Times the CPU oracle on a bounded sample of ciphertext indices of the same workload."""
+    from oracle import fedavg as ofed, scheme as osch
+    from oracle.params import Params
+    p = Params(w.log2_n, w.n_limbs, w.scale_bits, w.cbd_eta)
+    keys = osch.keygen(p, w.seed)
+    P = w.n_params
+    enc_idx, _ = ofed.mask_indices(P, runs)
+    n_ct = ofed.n_ciphertexts(p, len(enc_idx))
+
+    def one(c):
+        cts = [ofed.encrypt_ct(p, keys, x, enc_idx, w.seed, i, c)[1] for i, x in enumerate(ws_host)]
+        return ofed.decode_ct(p, keys, osch.aggregate(p, cts, alpha))
+
+    t0 = time.perf_counter()
+    one(0)
+    t_one = time.perf_counter() - t0
+    n_sample = int(max(1, min(n_ct - 1, budget_s // max(t_one, 1e-3))))
+    idx = np.linspace(1, n_ct - 1, n_sample).astype(int) if n_ct > 1 else np.array([0])
+    t0 = time.perf_counter()
+    for c in idx:
+        one(int(c))
+    dt = time.perf_counter() - t0
+    params = len(idx) * p.n_slots * len(ws_host)
+    return {"value": params / dt, "unit": "params/s", "cores": 1, "kind": "oracle",
+            "sample": f"{len(idx)} of {n_ct} ciphertext indices x {len(ws_host)} clients "
+                      f"(encrypt, aggregate, decrypt+decode), {dt:.1f} s, numpy single thread, "
+                      f"host has {os.cpu_count()} cores"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="resnet18_full")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (ciphertext indices are independent, so more GPUs "
+                 "would shard by ciphertext index with no collectives); run with --gpus 1")
+
+    import torch
+    from paper_2303_10837_amd import binding as he, synth_inputs as si
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    w = si.WORKLOADS[args.workload]
+    K = w.n_clients
+    ctx = he.Context(w.log2_n, w.n_limbs, w.scale_bits, w.cbd_eta)
+    keys = he.he_keygen(ctx, w.seed)
+    starts, lens = si.mask_runs(w)
+    runs = [(int(s), int(l)) for s, l in zip(starts, lens)]
+    mask = he.he_mask_create(ctx, w.n_params, starts, lens)
+    alpha = si.client_alphas(w)
+    ws_host = [si.client_params_numpy(w, i) for i in range(K)]
+    ws = [torch.from_numpy(x).cuda() for x in ws_host]
+    N, L, n_ct, P_enc = ctx.N, ctx.L, mask.n_ct, mask.P_enc
+    cts = [torch.empty((n_ct, 2, L, N), dtype=torch.int32, device="cuda") for _ in range(K)]
+    plains = [torch.empty((mask.n_plain,), dtype=torch.float32, device="cuda") for _ in range(K)]
+    ct_g = torch.empty((n_ct, 2, L - 1, N), dtype=torch.int32, device="cuda")
+    pl_g = torch.empty((mask.n_plain,), dtype=torch.float32, device="cuda")
+    out = torch.empty((w.n_params,), dtype=torch.float32, device="cuda")
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    phase_ms = np.zeros(3)
+
+    def step(record):
+        if record:
+            ev[0].record()
+        for i in range(K):
+            he.he_encrypt_masked(ctx, keys, mask, w.seed, i, ws[i], cts[i], plains[i])
+        if record:
+            ev[1].record()
+        he.he_aggregate(ctx, alpha, cts, plains, ct_g, pl_g)
+        if record:
+            ev[2].record()
+        he.he_decrypt_merge(ctx, keys, mask, ct_g, pl_g, out)
+        if record:
+            ev[3].record()
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    he.he_debug_timing_enable(ctx, True)
+    he.he_debug_timing_read(ctx)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+        ev[3].synchronize()   # phases of a step are read back while nothing else is queued
+        phase_ms += [ev[i].elapsed_time(ev[i + 1]) for i in range(3)]
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kern = he.he_debug_timing_read(ctx)
+    he.he_debug_timing_enable(ctx, False)
+    ms_step = dt * 1e3 / args.steps
+    phase_ms /= args.steps
+
+    # sanity: the decoded aggregate is FedAvg up to the CKKS noise (not part of the timing)
+    ref = sum(float(a) * x.double() for a, x in zip(alpha, ws))
+    max_err = float((out.double() - ref).abs().max())
+
+    # roofline of the dominant kernel (by accumulated device time)
+    enc_ms, enc_launches = kern["encrypt"]
+    agg_ms, agg_launches = kern["aggregate"]
+    enc_ops = encrypt_ops_per_ct(N, L) * n_ct * K * args.steps           # all launches of the timed region
+    enc_tops = enc_ops / (enc_ms * 1e-3) / 1e12 if enc_ms else 0.0
+    enc_bytes = (16 * L + 6) * N * n_ct * K * args.steps                 # ct written + m+e0, u, e1 read once
+    agg_bytes = n_ct * 2 * N * 4 * (K * L + (L - 1)) * args.steps
+    agg_gbs = agg_bytes / (agg_ms * 1e-3) / 1e9 if agg_ms else 0.0
+    dominant = max(kern, key=lambda k: kern[k][0])
+    roofline = {"kernel": "k_encrypt", "bound": "alu", "achieved": enc_tops, "peak": ALU_PEAK_TOPS, "unit": "TOP/s",
+                "frac": enc_tops / ALU_PEAK_TOPS, "traffic": None,
+                "avg_launch_ms": enc_ms / max(enc_launches, 1), "launches": int(enc_launches),
+                "hbm_GBps": enc_bytes / (enc_ms * 1e-3) / 1e9 if enc_ms else 0.0}
+    roofline_agg = {"kernel": "k_aggregate", "bound": "hbm", "achieved": agg_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": agg_gbs / HBM_PEAK_GBS, "traffic": None,
+                    "avg_launch_ms": agg_ms / max(agg_launches, 1), "launches": int(agg_launches)}
+
+    res = {
+        "metric": "encrypted params/sec (encrypt, aggregate, decrypt) + NTT/agg HBM GB/s % of peak",
+        "value": K * P_enc / (ms_step * 1e-3), "unit": "params/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u32", "data": "synthetic",
+        "config": {"workload": w.name, "clients": K, "params_per_client": w.n_params, "encrypted_params": P_enc,
+                   "n_ct_per_client": n_ct, "ring_degree": N, "limbs": L, "scale_bits": w.scale_bits,
+                   "value_definition": "clients * encrypted_params / step time; step = all clients encrypt + aggregate + decrypt"},
+        "phases": {"encrypt_ms": phase_ms[0], "aggregate_ms": phase_ms[1], "decrypt_ms": phase_ms[2],
+                   "encrypt_params_per_s": K * P_enc / (phase_ms[0] * 1e-3),
+                   "aggregate_params_per_s": P_enc / (phase_ms[1] * 1e-3),
+                   "decrypt_params_per_s": P_enc / (phase_ms[2] * 1e-3)},
+        "kernels_ms_per_step": {k: v[0] / args.steps for k, v in kern.items() if v[1]},
+        "dominant_kernel": dominant,
+        "roofline": roofline, "roofline_aggregate": roofline_agg,
+        "max_abs_err_vs_float64_fedavg": max_err,
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(w, ws_host, alpha, runs)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

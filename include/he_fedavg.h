@@ -190,6 +190,16 @@ he_status he_debug_ntt(he_ctx* ctx, int inverse, uint32_t limb, uint32_t* polys_
 he_status he_debug_export_keys(he_ctx* ctx, const he_pk* pk, const he_sk* sk,
                                uint32_t* pk_coeff_dev, int32_t* sk_coeff_dev, void* stream);
 
+/* Per-kernel device timing for benchmarks: while enabled, every kernel launch of this
+   context is bracketed by a pair of HIP events on its stream.  he_debug_timing_read waits
+   for the recorded events, writes the summed milliseconds and the launch count of each
+   kernel id (0 .. he_debug_timing_kernels()-1, named by he_debug_timing_name) to the host
+   arrays, and clears the record. */
+he_status he_debug_timing_enable(he_ctx* ctx, int on);
+uint32_t he_debug_timing_kernels(void);
+const char* he_debug_timing_name(uint32_t kernel_id);
+he_status he_debug_timing_read(he_ctx* ctx, double* ms_host, uint64_t* launches_host);
+
 #ifdef __cplusplus
 }
 #endif

@@ -58,6 +58,10 @@ _SIGS = {
     "he_debug_decode": (C.c_int32, [_P, _P, C.c_uint64, C.c_uint32, _P, _P]),
     "he_debug_ntt": (C.c_int32, [_P, C.c_int, C.c_uint32, _P, C.c_uint64, _P]),
     "he_debug_export_keys": (C.c_int32, [_P, _P, _P, _P, _P, _P]),
+    "he_debug_timing_enable": (C.c_int32, [_P, C.c_int]),
+    "he_debug_timing_kernels": (C.c_uint32, []),
+    "he_debug_timing_name": (C.c_char_p, [C.c_uint32]),
+    "he_debug_timing_read": (C.c_int32, [_P, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]),
 }
 
 EXPORTED_SYMBOLS = tuple(_SIGS)
@@ -303,3 +307,16 @@ def he_debug_export_keys(ctx, keys):
     sk = torch.empty((ctx.N,), dtype=torch.int32, device=ctx.device)
     _check(load().he_debug_export_keys(ctx.h, keys.pk, keys.sk, _ptr(pk), _ptr(sk), _stream()))
     return pk, sk
+
+
+def he_debug_timing_enable(ctx, on):
+    _check(load().he_debug_timing_enable(ctx.h, int(on)))
+
+
+def he_debug_timing_read(ctx):
+    """{kernel name: (total ms, launches)} since the last read."""
+    lib = load()
+    n = lib.he_debug_timing_kernels()
+    ms, cnt = (C.c_double * n)(), (C.c_uint64 * n)()
+    _check(lib.he_debug_timing_read(ctx.h, ms, cnt))
+    return {lib.he_debug_timing_name(i).decode(): (ms[i], cnt[i]) for i in range(n)}

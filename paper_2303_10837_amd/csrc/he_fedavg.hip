@@ -503,7 +503,22 @@ constexpr uint64_t kCtChunk = 1024;  // ciphertexts per scratch chunk
 
 }  // namespace
 
+enum KernelId : int {
+  KID_ENCODE = 0, KID_SAMPLE, KID_ENCRYPT, KID_AGGREGATE, KID_PLAIN_FEDAVG, KID_DECRYPT, KID_DECODE, KID_PLAIN_MOVE,
+  KID_NTT, KID_COUNT
+};
+static const char* const kKernelNames[KID_COUNT] = {"encode", "sample", "encrypt", "aggregate", "plain_fedavg",
+                                                    "decrypt", "decode", "plain_move", "ntt"};
+
+struct TimedSpan {
+  int kid;
+  hipEvent_t start, stop;
+};
+
 struct he_ctx {
+  bool timing_on = false;
+  std::vector<TimedSpan> spans;       // recorded, not yet read
+  std::vector<hipEvent_t> event_pool; // recycled events
   int device = 0;
   RingDev ring{};
   std::vector<uint32_t> primes;
@@ -533,6 +548,37 @@ struct he_mask {
 };
 
 namespace {
+
+// Brackets the launches issued during its lifetime with a pair of events on their stream
+// when per-kernel timing is enabled (measurement only; no effect otherwise).
+class KernelTimer {
+ public:
+  KernelTimer(he_ctx* ctx, int kid, hipStream_t st) : ctx_(ctx), st_(st) {
+    if (!ctx_->timing_on) return;
+    span_.kid = kid;
+    span_.start = take();
+    span_.stop = take();
+    live_ = span_.start && span_.stop && hipEventRecord(span_.start, st_) == hipSuccess;
+  }
+  ~KernelTimer() {
+    if (live_ && hipEventRecord(span_.stop, st_) == hipSuccess) ctx_->spans.push_back(span_);
+  }
+
+ private:
+  hipEvent_t take() {
+    if (!ctx_->event_pool.empty()) {
+      hipEvent_t e = ctx_->event_pool.back();
+      ctx_->event_pool.pop_back();
+      return e;
+    }
+    hipEvent_t e = nullptr;
+    return hipEventCreate(&e) == hipSuccess ? e : nullptr;
+  }
+  he_ctx* ctx_;
+  hipStream_t st_;
+  TimedSpan span_{};
+  bool live_ = false;
+};
 
 he_status ensure_ws(he_ctx* ctx, size_t bytes) {
   if (ctx->ws_bytes >= bytes) return HE_OK;
@@ -583,8 +629,11 @@ he_status check_ctx(const he_ctx* ctx) {
 he_status launch_encode(he_ctx* ctx, const MaskDev& mk, const float* w, const float* slots, uint64_t first_ct,
                         uint64_t n_ct, int32_t* m_out, hipStream_t st) {
   const uint32_t n = ctx->ring.N / 2;
-  hipLaunchKernelGGL(k_encode, dim3((uint32_t)n_ct), dim3(fft_threads(n)), fft_lds_bytes(n), st, ctx->ring, mk, w, slots,
-                     first_ct, m_out);
+  {
+    KernelTimer timer_(ctx, KID_ENCODE, st);
+    hipLaunchKernelGGL(k_encode, dim3((uint32_t)n_ct), dim3(fft_threads(n)), fft_lds_bytes(n), st, ctx->ring, mk, w, slots,
+                       first_ct, m_out);
+  }
   HIP_TRY(hipGetLastError());
   return HE_OK;
 }
@@ -594,10 +643,16 @@ he_status launch_sample_encrypt(he_ctx* ctx, const he_pk* pk, uint64_t seed, uin
                                 uint32_t* ct_out, hipStream_t st) {
   const RingDev& rg = ctx->ring;
   const uint2 key = make_uint2((uint32_t)seed, (uint32_t)(seed >> 32));
-  hipLaunchKernelGGL(k_sample, dim3((uint32_t)n_ct), dim3(256), 0, st, rg, key, client, first_ct, m_in, me0, u, e1);
+  {
+    KernelTimer timer_(ctx, KID_SAMPLE, st);
+    hipLaunchKernelGGL(k_sample, dim3((uint32_t)n_ct), dim3(256), 0, st, rg, key, client, first_ct, m_in, me0, u, e1);
+  }
   HIP_TRY(hipGetLastError());
-  hipLaunchKernelGGL(k_encrypt, dim3(rg.L, (uint32_t)n_ct), dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 2), st, rg,
-                     pk->tab, u, me0, e1, ct_out);
+  {
+    KernelTimer timer_(ctx, KID_ENCRYPT, st);
+    hipLaunchKernelGGL(k_encrypt, dim3(rg.L, (uint32_t)n_ct), dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 2), st, rg,
+                       pk->tab, u, me0, e1, ct_out);
+  }
   HIP_TRY(hipGetLastError());
   return HE_OK;
 }
@@ -605,8 +660,11 @@ he_status launch_sample_encrypt(he_ctx* ctx, const he_pk* pk, uint64_t seed, uin
 he_status launch_decrypt(he_ctx* ctx, const he_sk* sk, const uint32_t* ct, uint64_t n_ct, uint32_t level, uint32_t* d_out,
                          hipStream_t st) {
   const RingDev& rg = ctx->ring;
-  hipLaunchKernelGGL(k_decrypt, dim3(level, (uint32_t)n_ct), dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 1), st, rg,
-                     sk->tab, ct, level, d_out);
+  {
+    KernelTimer timer_(ctx, KID_DECRYPT, st);
+    hipLaunchKernelGGL(k_decrypt, dim3(level, (uint32_t)n_ct), dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 1), st, rg,
+                       sk->tab, ct, level, d_out);
+  }
   HIP_TRY(hipGetLastError());
   return HE_OK;
 }
@@ -623,6 +681,7 @@ he_status launch_decode(he_ctx* ctx, uint32_t level, const MaskDev& mk, const ui
                         float* w_out, double* slots_out, hipStream_t st) {
   CrtArgs ca{};
   he_host::modulus_words(ctx->primes.data(), level, ca.qw, ca.hw);
+  KernelTimer timer_(ctx, KID_DECODE, st);
   switch (level) {
     case 1: launch_decode_t<1>(ctx, ca, mk, d, first_ct, n_ct, w_out, slots_out, st); break;
     case 2: launch_decode_t<2>(ctx, ca, mk, d, first_ct, n_ct, w_out, slots_out, st); break;
@@ -661,6 +720,7 @@ he_status launch_agg(he_ctx* ctx, bool has_acc, bool fin, const AggArgs& a, uint
   const uint32_t log_n4 = rg.logN - 2;
   const uint64_t n_vec = (n_ct * 2) << log_n4;
   if (((n_vec + 255) / 256) > 0x7FFFFFFFull) return fail(HE_ERR_INVALID_ARG, "too many ciphertexts for one launch");
+  KernelTimer timer_(ctx, KID_AGGREGATE, st);
   switch (rg.L) {
     case 2: launch_agg_l<2>(has_acc, fin, a, ctx->agg, log_n4, n_vec, acc_in, out, st); break;
     case 3: launch_agg_l<3>(has_acc, fin, a, ctx->agg, log_n4, n_vec, acc_in, out, st); break;
@@ -675,10 +735,11 @@ he_status launch_agg(he_ctx* ctx, bool has_acc, bool fin, const AggArgs& a, uint
   return HE_OK;
 }
 
-he_status launch_plain(bool has_acc, bool fin, const PlainArgs& a, uint64_t n_plain, const double* acc_in, double* acc_out,
-                       float* out, hipStream_t st) {
+he_status launch_plain(he_ctx* ctx, bool has_acc, bool fin, const PlainArgs& a, uint64_t n_plain, const double* acc_in,
+                       double* acc_out, float* out, hipStream_t st) {
   if (n_plain == 0) return HE_OK;
   const dim3 grid(grid_for(n_plain, 256)), block(256);
+  KernelTimer timer_(ctx, KID_PLAIN_FEDAVG, st);
   if (has_acc && fin) hipLaunchKernelGGL((k_plain_fedavg<true, true>), grid, block, 0, st, a, n_plain, acc_in, acc_out, out);
   else if (has_acc) hipLaunchKernelGGL((k_plain_fedavg<true, false>), grid, block, 0, st, a, n_plain, acc_in, acc_out, out);
   else if (fin) hipLaunchKernelGGL((k_plain_fedavg<false, true>), grid, block, 0, st, a, n_plain, acc_in, acc_out, out);
@@ -726,7 +787,7 @@ he_status aggregate_impl(he_ctx* ctx, uint32_t K, const double* alpha, const std
     const bool do_fin = fin && last;
     he_status s = launch_agg(ctx, acc_live, do_fin, a, n_ct, acc_ct, do_fin ? ct_out : acc_ct, st);
     if (s != HE_OK) return s;
-    s = launch_plain(acc_live, do_fin, pa, n_plain, acc_plain, acc_plain, plain_out, st);
+    s = launch_plain(ctx, acc_live, do_fin, pa, n_plain, acc_plain, acc_plain, plain_out, st);
     if (s != HE_OK) return s;
     acc_live = true;
     done += kc;
@@ -854,6 +915,11 @@ void he_ctx_destroy(he_ctx* ctx) {
   (void)hipDeviceSynchronize();
   for (void* p : ctx->dev_allocs) (void)hipFree(p);
   if (ctx->ws) (void)hipFree(ctx->ws);
+  for (const TimedSpan& sp : ctx->spans) {
+    (void)hipEventDestroy(sp.start);
+    (void)hipEventDestroy(sp.stop);
+  }
+  for (hipEvent_t e : ctx->event_pool) (void)hipEventDestroy(e);
   delete ctx;
 }
 
@@ -1064,6 +1130,7 @@ he_status he_encrypt_masked(he_ctx* ctx, const he_pk* pk, const he_mask* mask, u
     if (s != HE_OK) return s;
   }
   if (n_plain) {
+    KernelTimer timer_(ctx, KID_PLAIN_MOVE, st);
     hipLaunchKernelGGL(k_plain_move<false>, dim3(grid_for(n_plain, 256, 1u << 16)), dim3(256), 0, st, mk, w_dev, plain_out_dev);
     HIP_TRY(hipGetLastError());
   }
@@ -1147,7 +1214,7 @@ he_status he_aggregate_finalize(he_ctx* ctx, uint64_t n_ct, uint64_t n_plain, co
   PlainArgs pa{};
   s = launch_agg(ctx, true, true, a, n_ct, acc_ct_dev, ct_out_dev, st);
   if (s != HE_OK) return s;
-  return launch_plain(true, true, pa, n_plain, acc_plain_dev, nullptr, plain_out_dev, st);
+  return launch_plain(ctx, true, true, pa, n_plain, acc_plain_dev, nullptr, plain_out_dev, st);
 }
 
 // ---- client: decrypt + merge -----------------------------------------------------------
@@ -1178,6 +1245,7 @@ he_status he_decrypt_merge(he_ctx* ctx, const he_sk* sk, const he_mask* mask, co
     if (s != HE_OK) return s;
   }
   if (n_plain) {
+    KernelTimer timer_(ctx, KID_PLAIN_MOVE, st);
     hipLaunchKernelGGL(k_plain_move<true>, dim3(grid_for(n_plain, 256, 1u << 16)), dim3(256), 0, st, mk, plain_glob_dev, w_out_dev);
     HIP_TRY(hipGetLastError());
   }
@@ -1261,6 +1329,7 @@ he_status he_debug_ntt(he_ctx* ctx, int inverse, uint32_t limb, uint32_t* polys_
   if (batch >= (1ull << 31)) return fail(HE_ERR_INVALID_ARG, "batch too large");
   const RingDev& rg = ctx->ring;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  KernelTimer timer_(ctx, KID_NTT, st);
   if (inverse)
     hipLaunchKernelGGL(k_ntt_batch<true>, dim3((uint32_t)batch), dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 1), st, rg, (int)limb, polys_dev);
   else
@@ -1286,6 +1355,37 @@ he_status he_debug_export_keys(he_ctx* ctx, const he_pk* pk, const he_sk* sk, ui
     hipLaunchKernelGGL(k_widen_i8, dim3((rg.N + 255) / 256), dim3(256), 0, st, sk->coeff, sk_coeff_dev, rg.N);
     HIP_TRY(hipGetLastError());
   }
+  return HE_OK;
+}
+
+he_status he_debug_timing_enable(he_ctx* ctx, int on) {
+  if (!ctx) return fail(HE_ERR_INVALID_ARG, "context is null");
+  ctx->timing_on = on != 0;
+  return HE_OK;
+}
+
+uint32_t he_debug_timing_kernels(void) { return KID_COUNT; }
+
+const char* he_debug_timing_name(uint32_t kernel_id) { return kernel_id < KID_COUNT ? kKernelNames[kernel_id] : ""; }
+
+he_status he_debug_timing_read(he_ctx* ctx, double* ms_host, uint64_t* launches_host) {
+  he_status s = check_ctx(ctx);
+  if (s != HE_OK) return s;
+  if (!ms_host || !launches_host) return fail(HE_ERR_INVALID_ARG, "null argument");
+  for (int k = 0; k < KID_COUNT; ++k) {
+    ms_host[k] = 0.0;
+    launches_host[k] = 0;
+  }
+  for (const TimedSpan& sp : ctx->spans) {
+    HIP_TRY(hipEventSynchronize(sp.stop));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, sp.start, sp.stop));
+    ms_host[sp.kid] += ms;
+    launches_host[sp.kid] += 1;
+    ctx->event_pool.push_back(sp.start);
+    ctx->event_pool.push_back(sp.stop);
+  }
+  ctx->spans.clear();
   return HE_OK;
 }
 
