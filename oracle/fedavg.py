@@ -106,3 +106,32 @@ def noise_sigma(p: Params, alpha):
     var_coeff = var_fresh * float(np.sum(np.asarray(alpha, dtype=np.float64) ** 2)) \
         + (1.0 + 2.0 * n_ring / 3.0) / 12.0 + 1.0 / 12.0
     return float(np.sqrt(n_ring * var_coeff / 2.0)) / p.delta
+
+
+def packed_to_param(starts, lens, t):
+    """Parameter index of packed positions t (array) under the run list (starts, lens).
+
+    Same map as mask_indices()[0][t], computed from the runs' prefix sums, so that it also
+    works for vectors too long to enumerate."""
+    starts = np.asarray(starts, dtype=np.int64)
+    lens = np.asarray(lens, dtype=np.int64)
+    prefix = np.concatenate([[0], np.cumsum(lens)])
+    t = np.asarray(t, dtype=np.int64)
+    assert t.size == 0 or (t.min() >= 0 and t.max() < prefix[-1])
+    r = np.searchsorted(prefix, t, side="right") - 1
+    return starts[r] + (t - prefix[r])
+
+
+def complement_runs(P: int, starts, lens):
+    """Run list of the unmasked remainder."""
+    out_s, out_l, pos = [], [], 0
+    for s, ln in zip(starts, lens):
+        s, ln = int(s), int(ln)
+        if s > pos:
+            out_s.append(pos)
+            out_l.append(s - pos)
+        pos = s + ln
+    if pos < P:
+        out_s.append(pos)
+        out_l.append(P - pos)
+    return np.asarray(out_s, dtype=np.int64), np.asarray(out_l, dtype=np.int64)

@@ -1,0 +1,177 @@
+"""GPU parity at the full sizes of the five benchmark workloads, in the launch configuration
+bench.py times (K x he_encrypt_masked, he_aggregate, he_decrypt_merge over whole models).
+
+The oracle cannot run a whole model, so each workload checks
+  * sampled ciphertext indices (first, chunk boundaries, middle, the ragged last one) of sampled
+    clients, bit for bit, through every stage -- every ciphertext is an independent function of
+    (seed, client, index), so sampling is exact, not approximate;
+  * the plaintext remainder over the whole vector (bit-exact against a float64 torch evaluation
+    of the same formula, and against the numpy oracle on sampled ranges);
+  * error statistics of the whole decoded model against float64 FedAvg under the CKKS noise model.
+"""
+import gc
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import encoder as oenc
+from oracle import fedavg as ofed
+from oracle import scheme as osch
+from oracle.params import Params
+from paper_2303_10837_amd import synth_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def he():
+    from paper_2303_10837_amd import binding
+    binding.load()
+    torch.cuda.set_device(0)
+    return binding
+
+
+def _sample_cts(n_ct, extra=2, seed=0):
+    cand = {0, n_ct - 1, n_ct // 2, 1023, 1024, n_ct - 2}
+    rs = np.random.default_rng(seed)
+    cand |= set(int(x) for x in rs.integers(0, n_ct, extra))
+    return sorted(c for c in cand if 0 <= c < n_ct)
+
+
+def _run_workload(he, w, device_inputs, stream_plain, clients_checked, cts_extra):
+    print(f"\n[{w.name}] K={w.n_clients} P={w.n_params} N=2^{w.log2_n} L={w.n_limbs}", flush=True)
+    K, P = w.n_clients, w.n_params
+    p = Params(w.log2_n, w.n_limbs, w.scale_bits, w.cbd_eta)
+    ctx = he.Context(w.log2_n, w.n_limbs, w.scale_bits, w.cbd_eta)
+    keys = he.he_keygen(ctx, w.seed)
+    okeys = osch.keygen(p, w.seed)
+    starts, lens = si.mask_runs(w)
+    mask = he.he_mask_create(ctx, P, starts, lens)
+    alpha = si.client_alphas(w)
+    n, N, L = p.n_slots, p.N, p.n_limbs
+    n_ct, P_enc, n_plain = mask.n_ct, mask.P_enc, mask.n_plain
+    assert P_enc == int(lens.sum()) and n_ct == -(-P_enc // n)
+    sample = _sample_cts(n_ct, cts_extra, w.seed)
+    cstarts, clens = ofed.complement_runs(P, starts, lens)
+
+    # positions the oracle needs from each client's vector
+    def packed_idx(c):
+        t = np.arange(c * n, min((c + 1) * n, P_enc))
+        return ofed.packed_to_param(starts, lens, t)
+
+    plain_probe = np.unique(np.concatenate([np.arange(0, min(n_plain, 4096)),
+                                            np.arange(max(0, n_plain - 4096), n_plain),
+                                            np.random.default_rng(1).integers(0, max(n_plain, 1), 4096)])) if n_plain else np.zeros(0, dtype=np.int64)
+    plain_probe_param = ofed.packed_to_param(cstarts, clens, plain_probe) if n_plain else plain_probe
+
+    cts, slots_host, plain_host = [], {}, []
+    ref64 = torch.zeros(P, dtype=torch.float64, device="cuda")            # float64 FedAvg of everything
+    acc_plain = acc_none = None
+    plains = []
+    if stream_plain and n_plain:
+        acc_none, acc_plain = he.he_aggregate_begin(ctx, 0, n_plain)      # plain part only: no ciphertext accumulator
+    plain_ref64 = torch.zeros(n_plain, dtype=torch.float64, device="cuda") if n_plain else None
+    for i in range(K):
+        wi = si.client_params_torch(w, i, "cuda") if device_inputs else torch.from_numpy(si.client_params_numpy(w, i)).cuda()
+        ct, pl = he.he_encrypt_masked(ctx, keys, mask, w.seed, i, wi)
+        cts.append(ct)
+        ref64 += float(alpha[i]) * wi.double()
+        if i in clients_checked:
+            for c in sample:
+                slots_host[(i, c)] = wi[torch.from_numpy(packed_idx(c)).cuda()].cpu().numpy()
+        if n_plain:
+            plain_host.append(wi[torch.from_numpy(plain_probe_param).cuda()].cpu().numpy())
+            # the compaction itself, over the whole vector
+            assert torch.equal(pl[torch.from_numpy(plain_probe).cuda()].cpu(), torch.from_numpy(plain_host[-1]))
+            prod = float(alpha[i]) * pl.double()
+            plain_ref64 = plain_ref64 + prod
+            del prod
+            if stream_plain:
+                he.he_aggregate_add(ctx, alpha[i:i + 1], [None], [pl], acc_none, acc_plain)
+            else:
+                plains.append(pl)
+        del wi
+        if stream_plain:
+            del pl
+    print(f"[{w.name}] encrypted {K} x {n_ct} ciphertexts", flush=True)
+
+    # ---- server ----
+    if stream_plain and n_plain:
+        ct_g, _ = he.he_aggregate(ctx, alpha, cts, [None] * K)
+        _, pl_g = he.he_aggregate_finalize(ctx, acc_none, acc_plain)
+    else:
+        ct_g, pl_g = he.he_aggregate(ctx, alpha, cts, plains if n_plain else [None] * K)
+    out = he.he_decrypt_merge(ctx, keys, mask, ct_g, pl_g if n_plain else None)
+    torch.cuda.synchronize()
+    print(f"[{w.name}] aggregated and decrypted", flush=True)
+
+    # ---- sampled ciphertexts, stage by stage ----
+    for c in sample:
+        live = min(n, P_enc - c * n)
+        for i in clients_checked:
+            z = np.zeros(n, dtype=np.float32)
+            z[:live] = slots_host[(i, c)]
+            m_gpu = he.he_debug_encode(ctx, torch.from_numpy(z[None]).cuda())[0].cpu().numpy().astype(np.int64)
+            assert np.abs(m_gpu - oenc.encode_fft(z.astype(np.float64), w.log2_n, w.scale_bits)).max() <= 1
+            ref = osch.encrypt(p, okeys, m_gpu, w.seed, i, c)
+            assert np.array_equal(cts[i][c].cpu().numpy().astype(np.int64), ref), (w.name, i, c)
+        # aggregation of all K clients' ciphertext c (inputs are the GPU's, just verified for the sampled clients)
+        ct_c = [cts[i][c].cpu().numpy().astype(np.int64) for i in range(K)]
+        agg = osch.aggregate(p, ct_c, alpha)
+        assert np.array_equal(ct_g[c].cpu().numpy().astype(np.int64), agg), (w.name, c)
+        zdec = ofed.decode_ct(p, okeys, agg)
+        got = out[torch.from_numpy(packed_idx(c)).cuda()].cpu().numpy()
+        assert np.abs(got.astype(np.float64) - zdec[:live].astype(np.float32).astype(np.float64)).max() <= 1e-6, (w.name, c)
+    print(f"[{w.name}] {len(sample)} sampled ciphertext indices x {len(clients_checked)} clients bit-exact", flush=True)
+
+    # ---- plaintext remainder ----
+    if n_plain:
+        assert torch.equal(pl_g, plain_ref64.float()), "plain FedAvg differs from the float64 evaluation"
+        assert np.array_equal(pl_g[torch.from_numpy(plain_probe).cuda()].cpu().numpy(), ofed.plain_fedavg(plain_host, alpha))
+        assert torch.equal(out[torch.from_numpy(plain_probe_param).cuda()], pl_g[torch.from_numpy(plain_probe).cuda()])
+    # ---- whole model against float64 FedAvg ----
+    is_enc = torch.zeros(P, dtype=torch.bool, device="cuda")
+    for s, ln in zip(starts, lens):
+        is_enc[int(s):int(s) + int(ln)] = True
+    err = out.double() - ref64
+    if n_plain:
+        assert torch.equal(out[~is_enc], ref64[~is_enc].float())
+    e = err[is_enc]
+    sigma = ofed.noise_sigma(p, alpha)
+    rms, mx = float(e.pow(2).mean().sqrt()), float(e.abs().max())
+    print(f"[{w.name}] vs float64 FedAvg on {int(is_enc.sum())} encrypted params: rms {rms:.3e} max {mx:.3e} (model sigma {sigma:.3e})", flush=True)
+    assert 0.7 * sigma < rms < 1.4 * sigma and mx < 16 * sigma
+    del cts, ct_g, out, ref64, err, is_enc, plains, pl_g, plain_ref64, acc_plain
+    keys.close()
+    mask.close()
+    ctx.close()
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
+def test_tiny_full(he):
+    _run_workload(he, si.WORKLOADS["tiny_full"], False, False, clients_checked=[0, 1, 2], cts_extra=30)
+
+
+def test_resnet18_full(he):
+    _run_workload(he, si.WORKLOADS["resnet18_full"], False, False, clients_checked=[0, 7], cts_extra=2)
+
+
+def test_resnet50_sel10(he):
+    _run_workload(he, si.WORKLOADS["resnet50_sel10"], False, False, clients_checked=[3, 15], cts_extra=2)
+
+
+def test_bert_sel10(he):
+    _run_workload(he, si.WORKLOADS["bert_sel10"], True, False, clients_checked=[0, 5], cts_extra=2)
+
+
+def test_bert_full(he):
+    _run_workload(he, si.WORKLOADS["bert_full"], True, False, clients_checked=[2], cts_extra=1)
+
+
+def test_fm1p3b_sel5(he):
+    free, _ = torch.cuda.mem_get_info()
+    if free < 200 * 2 ** 30:
+        pytest.skip("needs about 180 GiB of free HBM")
+    _run_workload(he, si.WORKLOADS["fm1p3b_sel5"], True, True, clients_checked=[0, 31], cts_extra=1)

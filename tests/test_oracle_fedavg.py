@@ -64,3 +64,18 @@ def test_synthetic_workload_recipes():
     assert np.array_equal(x, si.client_params_numpy(w, 1)) and not np.array_equal(x, si.client_params_numpy(w, 2))
     x = si.client_params_numpy(si.WORKLOADS["tiny_full"], 0)
     assert abs(x.std() - 0.05) < 0.002
+
+
+def test_run_list_lookup_matches_enumeration():
+    rs = np.random.default_rng(3)
+    P = 5000
+    for trial in range(5):
+        cuts = np.sort(rs.choice(np.arange(1, P), size=20, replace=False))
+        bounds = np.concatenate([[0], cuts, [P]])
+        runs = [(int(bounds[i]), int(bounds[i + 1] - bounds[i])) for i in range(trial % 2, len(bounds) - 1, 2)]
+        starts, lens = [r[0] for r in runs], [r[1] for r in runs]
+        enc_idx, plain_idx = fedavg.mask_indices(P, runs)
+        t = np.arange(len(enc_idx))
+        assert np.array_equal(fedavg.packed_to_param(starts, lens, t), enc_idx)
+        cs, cl = fedavg.complement_runs(P, starts, lens)
+        assert np.array_equal(fedavg.packed_to_param(cs, cl, np.arange(len(plain_idx))), plain_idx)
