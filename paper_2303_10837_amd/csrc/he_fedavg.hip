@@ -13,6 +13,7 @@
 #include "he_device.hpp"
 #include "he_fedavg.h"
 #include "he_host_tables.hpp"
+#include "he_ntt_static.hpp"
 
 using namespace he;
 
@@ -213,6 +214,193 @@ k_decrypt(RingDev rg, const uint2* __restrict__ sk, const uint32_t* __restrict__
   ntt_inverse_from(
       buf, logN, rg.tw_inv + (size_t)j * N, q, [=](int a) { return mul_shoup(buf[lds_pad(a)], key[a], q); },
       [=](int a, uint32_t v) { out[a] = add_mod(v, c0[a], q); });
+}
+
+// ---- compile-time specialised versions of the three transform kernels (N = 2^13, 2^14) ----
+// Same results as k_encrypt / k_decrypt / k_ntt_batch; see he_ntt_static.hpp for the plan.
+
+__device__ __forceinline__ void load_key8(const uint2* __restrict__ key, int base, uint2 (&k)[8]) {
+  const uint4* p = reinterpret_cast<const uint4*>(key + base);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint4 t = p[i];
+    k[2 * i] = make_uint2(t.x, t.y);
+    k[2 * i + 1] = make_uint2(t.z, t.w);
+  }
+}
+
+template <int LOGN>
+__global__ void __launch_bounds__(NttPlan<LOGN>::NT)
+k_encrypt_s(RingDev rg, const uint2* __restrict__ pk, const int8_t* __restrict__ u, const int32_t* __restrict__ me0,
+            const int8_t* __restrict__ e1, uint32_t* __restrict__ ct_out) {
+  using P = NttPlan<LOGN>;
+  constexpr int N = 1 << LOGN;
+  extern __shared__ uint32_t lds_u[];
+  uint32_t* A = lds_u;
+  uint32_t* B = lds_u + spad(N);
+  const uint32_t L = rg.L;
+  const uint32_t j = blockIdx.x;
+  const uint64_t c = blockIdx.y;
+  const uint32_t q = rg.q[j];
+  const uint2* twf = rg.tw_fwd + (size_t)j * N;
+  const uint2* twi = rg.tw_inv + (size_t)j * N;
+  const int8_t* uc = u + c * N;
+  fwd_head<LOGN>(A, twf, q, [=](int a) {
+    const int v = uc[a];
+    return (uint32_t)(v < 0 ? v + (int)q : v);
+  });
+  {  // forward pass 3, product with b^ and a^, inverse pass 3: all on the same 8 coefficients
+    constexpr int S0 = P::S[3], R = P::R[3];
+    static_assert(R == 3, "the fused middle pass works on groups of 8");
+    using G = PassGeom<LOGN, S0, R>;
+    const uint2* kb = pk + ((size_t)0 * L + j) * N;
+    const uint2* ka = pk + ((size_t)1 * L + j) * N;
+    for (int g = threadIdx.x; g < G::GROUPS; g += P::NT) {
+      uint32_t v[1][8];
+      lds_load_group<LOGN, S0, R>(A, g, v[0]);
+      bfly_stages<LOGN, S0, R, false, 1>(v, g, twf, q);
+      uint2 k0[8], k1[8];
+      load_key8(kb, g << 3, k0);
+      load_key8(ka, g << 3, k1);
+      uint32_t w[2][8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        w[0][i] = mul_shoup(v[0][i], k0[i], q);
+        w[1][i] = mul_shoup(v[0][i], k1[i], q);
+      }
+      bfly_stages<LOGN, S0, R, true, 2>(w, g, twi, q);
+      lds_store_group<LOGN, S0, R>(A, g, w[0]);
+      lds_store_group<LOGN, S0, R>(B, g, w[1]);
+    }
+  }
+  __syncthreads();
+  uint32_t* const xs[2] = {A, B};
+  inv_middle<LOGN, 2>(xs, twi, q);
+  {  // inverse pass 0, + (m + e0) / + e1, store
+    constexpr int R = P::R[0];
+    using G = PassGeom<LOGN, 0, R>;
+    const int32_t* mc = me0 + c * N;
+    const int8_t* ec = e1 + c * N;
+    uint32_t* out0 = ct_out + ((c * 2 + 0) * L + j) * N;
+    uint32_t* out1 = ct_out + ((c * 2 + 1) * L + j) * N;
+    for (int g = threadIdx.x; g < G::GROUPS; g += P::NT) {
+      uint32_t v[2][1 << R];
+      lds_load_group<LOGN, 0, R>(A, g, v[0]);
+      lds_load_group<LOGN, 0, R>(B, g, v[1]);
+      bfly_stages<LOGN, 0, R, true, 2>(v, 0, twi, q);
+#pragma unroll
+      for (int i = 0; i < G::E; ++i) {
+        const int a = g + (i << G::LSTRIDE);
+        out0[a] = add_mod(v[0][i], residue_of_signed(mc[a], q), q);
+        out1[a] = add_mod(v[1][i], residue_of_signed((int32_t)ec[a], q), q);
+      }
+    }
+  }
+}
+
+template <int LOGN>
+__global__ void __launch_bounds__(NttPlan<LOGN>::NT)
+k_decrypt_s(RingDev rg, const uint2* __restrict__ sk, const uint32_t* __restrict__ ct, uint32_t level,
+            uint32_t* __restrict__ d_out) {
+  using P = NttPlan<LOGN>;
+  constexpr int N = 1 << LOGN;
+  extern __shared__ uint32_t lds_u[];
+  uint32_t* A = lds_u;
+  const uint32_t j = blockIdx.x;
+  const uint64_t c = blockIdx.y;
+  const uint32_t q = rg.q[j];
+  const uint2* twf = rg.tw_fwd + (size_t)j * N;
+  const uint2* twi = rg.tw_inv + (size_t)j * N;
+  const uint32_t* c0 = ct + ((c * 2 + 0) * level + j) * N;
+  const uint32_t* c1 = ct + ((c * 2 + 1) * level + j) * N;
+  uint32_t* out = d_out + (c * level + j) * N;
+  const uint2* key = sk + (size_t)j * N;
+  fwd_head<LOGN>(A, twf, q, [=](int a) { return c1[a]; });
+  {
+    constexpr int S0 = P::S[3], R = P::R[3];
+    static_assert(R == 3, "the fused middle pass works on groups of 8");
+    using G = PassGeom<LOGN, S0, R>;
+    for (int g = threadIdx.x; g < G::GROUPS; g += P::NT) {
+      uint32_t v[1][8];
+      lds_load_group<LOGN, S0, R>(A, g, v[0]);
+      bfly_stages<LOGN, S0, R, false, 1>(v, g, twf, q);
+      uint2 k0[8];
+      load_key8(key, g << 3, k0);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[0][i] = mul_shoup(v[0][i], k0[i], q);
+      bfly_stages<LOGN, S0, R, true, 1>(v, g, twi, q);
+      lds_store_group<LOGN, S0, R>(A, g, v[0]);
+    }
+  }
+  __syncthreads();
+  uint32_t* const xs[1] = {A};
+  inv_middle<LOGN, 1>(xs, twi, q);
+  {
+    constexpr int R = P::R[0];
+    using G = PassGeom<LOGN, 0, R>;
+    for (int g = threadIdx.x; g < G::GROUPS; g += P::NT) {
+      uint32_t v[1][1 << R];
+      lds_load_group<LOGN, 0, R>(A, g, v[0]);
+      bfly_stages<LOGN, 0, R, true, 1>(v, 0, twi, q);
+#pragma unroll
+      for (int i = 0; i < G::E; ++i) {
+        const int a = g + (i << G::LSTRIDE);
+        out[a] = add_mod(v[0][i], c0[a], q);
+      }
+    }
+  }
+}
+
+template <int LOGN, bool INV>
+__global__ void __launch_bounds__(NttPlan<LOGN>::NT)
+k_ntt_batch_s(RingDev rg, int limb, uint32_t* __restrict__ polys) {
+  using P = NttPlan<LOGN>;
+  constexpr int N = 1 << LOGN;
+  extern __shared__ uint32_t lds_u[];
+  uint32_t* A = lds_u;
+  const uint32_t j = limb >= 0 ? (uint32_t)limb : (uint32_t)(blockIdx.x % rg.L);
+  const uint32_t q = rg.q[j];
+  uint32_t* x = polys + (size_t)blockIdx.x * N;
+  constexpr int S3 = P::S[3], R3 = P::R[3];
+  using G3 = PassGeom<LOGN, S3, R3>;
+  if (!INV) {
+    const uint2* twf = rg.tw_fwd + (size_t)j * N;
+    fwd_head<LOGN>(A, twf, q, [=](int a) { return x[a]; });
+    for (int g = threadIdx.x; g < G3::GROUPS; g += P::NT) {
+      uint32_t v[1][1 << R3];
+      lds_load_group<LOGN, S3, R3>(A, g, v[0]);
+      bfly_stages<LOGN, S3, R3, false, 1>(v, g, twf, q);
+      uint4* o = reinterpret_cast<uint4*>(x + (g << R3));
+#pragma unroll
+      for (int i = 0; i < (1 << R3); i += 4) o[i >> 2] = make_uint4(v[0][i], v[0][i + 1], v[0][i + 2], v[0][i + 3]);
+    }
+  } else {
+    const uint2* twi = rg.tw_inv + (size_t)j * N;
+    const uint2 ninv = rg.ninv[j];
+    for (int g = threadIdx.x; g < G3::GROUPS; g += P::NT) {
+      uint32_t v[1][1 << R3];
+      const uint4* in = reinterpret_cast<const uint4*>(x + (g << R3));
+#pragma unroll
+      for (int i = 0; i < (1 << R3); i += 4) {
+        const uint4 t = in[i >> 2];
+        v[0][i] = t.x; v[0][i + 1] = t.y; v[0][i + 2] = t.z; v[0][i + 3] = t.w;
+      }
+      bfly_stages<LOGN, S3, R3, true, 1>(v, g, twi, q);
+      lds_store_group<LOGN, S3, R3>(A, g, v[0]);
+    }
+    __syncthreads();
+    uint32_t* const xs[1] = {A};
+    inv_middle<LOGN, 1>(xs, twi, q);
+    constexpr int R0 = P::R[0];
+    using G0 = PassGeom<LOGN, 0, R0>;
+    for (int g = threadIdx.x; g < G0::GROUPS; g += P::NT) {
+      uint32_t v[1][1 << R0];
+      lds_load_group<LOGN, 0, R0>(A, g, v[0]);
+      bfly_stages<LOGN, 0, R0, true, 1>(v, 0, twi, q);
+#pragma unroll
+      for (int i = 0; i < G0::E; ++i) x[g + (i << G0::LSTRIDE)] = mul_shoup(v[0][i], ninv, q);
+    }
+  }
 }
 
 // ---- a9: CRT lift (Garner), exact centring, conversion to fp64 ---------------------------
@@ -607,6 +795,10 @@ int ntt_threads(uint32_t N) { return (int)std::min<uint32_t>(1024, std::max<uint
 int fft_threads(uint32_t n) { return (int)std::min<uint32_t>(1024, std::max<uint32_t>(64, n >> 2)); }
 size_t ntt_lds_bytes(uint32_t N, int bufs) { return (size_t)bufs * lds_pad((int)N) * sizeof(uint32_t); }
 size_t fft_lds_bytes(uint32_t n) { return (size_t)2 * n * sizeof(double); }
+size_t static_lds_bytes(int logN, int bufs) { return (size_t)bufs * spad(1 << logN) * sizeof(uint32_t); }
+
+// Batched standalone transform: specialised kernels for the tuned sizes, generic otherwise.
+void launch_ntt_batch(const RingDev& rg, bool inverse, int limb, uint32_t* polys, uint32_t batch, hipStream_t st);
 
 template <class K>
 he_status allow_lds(K kernel, size_t bytes) {
@@ -625,6 +817,20 @@ he_status check_ctx(const he_ctx* ctx) {
 }
 
 // ---- shared launch helpers ---------------------------------------------------------------
+
+void launch_ntt_batch(const RingDev& rg, bool inverse, int limb, uint32_t* polys, uint32_t batch, hipStream_t st) {
+  const dim3 grid(batch);
+  if (rg.logN == 14) {
+    if (inverse) hipLaunchKernelGGL((k_ntt_batch_s<14, true>), grid, dim3(NttPlan<14>::NT), static_lds_bytes(14, 1), st, rg, limb, polys);
+    else hipLaunchKernelGGL((k_ntt_batch_s<14, false>), grid, dim3(NttPlan<14>::NT), static_lds_bytes(14, 1), st, rg, limb, polys);
+  } else if (rg.logN == 13) {
+    if (inverse) hipLaunchKernelGGL((k_ntt_batch_s<13, true>), grid, dim3(NttPlan<13>::NT), static_lds_bytes(13, 1), st, rg, limb, polys);
+    else hipLaunchKernelGGL((k_ntt_batch_s<13, false>), grid, dim3(NttPlan<13>::NT), static_lds_bytes(13, 1), st, rg, limb, polys);
+  } else {
+    if (inverse) hipLaunchKernelGGL(k_ntt_batch<true>, grid, dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 1), st, rg, limb, polys);
+    else hipLaunchKernelGGL(k_ntt_batch<false>, grid, dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 1), st, rg, limb, polys);
+  }
+}
 
 he_status launch_encode(he_ctx* ctx, const MaskDev& mk, const float* w, const float* slots, uint64_t first_ct,
                         uint64_t n_ct, int32_t* m_out, hipStream_t st) {
@@ -650,8 +856,13 @@ he_status launch_sample_encrypt(he_ctx* ctx, const he_pk* pk, uint64_t seed, uin
   HIP_TRY(hipGetLastError());
   {
     KernelTimer timer_(ctx, KID_ENCRYPT, st);
-    hipLaunchKernelGGL(k_encrypt, dim3(rg.L, (uint32_t)n_ct), dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 2), st, rg,
-                       pk->tab, u, me0, e1, ct_out);
+    const dim3 grid(rg.L, (uint32_t)n_ct);
+    if (rg.logN == 14)
+      hipLaunchKernelGGL(k_encrypt_s<14>, grid, dim3(NttPlan<14>::NT), static_lds_bytes(14, 2), st, rg, pk->tab, u, me0, e1, ct_out);
+    else if (rg.logN == 13)
+      hipLaunchKernelGGL(k_encrypt_s<13>, grid, dim3(NttPlan<13>::NT), static_lds_bytes(13, 2), st, rg, pk->tab, u, me0, e1, ct_out);
+    else
+      hipLaunchKernelGGL(k_encrypt, grid, dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 2), st, rg, pk->tab, u, me0, e1, ct_out);
   }
   HIP_TRY(hipGetLastError());
   return HE_OK;
@@ -662,8 +873,13 @@ he_status launch_decrypt(he_ctx* ctx, const he_sk* sk, const uint32_t* ct, uint6
   const RingDev& rg = ctx->ring;
   {
     KernelTimer timer_(ctx, KID_DECRYPT, st);
-    hipLaunchKernelGGL(k_decrypt, dim3(level, (uint32_t)n_ct), dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 1), st, rg,
-                       sk->tab, ct, level, d_out);
+    const dim3 grid(level, (uint32_t)n_ct);
+    if (rg.logN == 14)
+      hipLaunchKernelGGL(k_decrypt_s<14>, grid, dim3(NttPlan<14>::NT), static_lds_bytes(14, 1), st, rg, sk->tab, ct, level, d_out);
+    else if (rg.logN == 13)
+      hipLaunchKernelGGL(k_decrypt_s<13>, grid, dim3(NttPlan<13>::NT), static_lds_bytes(13, 1), st, rg, sk->tab, ct, level, d_out);
+    else
+      hipLaunchKernelGGL(k_decrypt, grid, dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 1), st, rg, sk->tab, ct, level, d_out);
   }
   HIP_TRY(hipGetLastError());
   return HE_OK;
@@ -893,6 +1109,14 @@ he_status he_ctx_create(const he_params* params, int device, he_ctx** out) {
   if (s == HE_OK) s = allow_lds(k_decrypt, ntt_lds_bytes(N, 1));
   if (s == HE_OK) s = allow_lds(k_ntt_batch<false>, ntt_lds_bytes(N, 1));
   if (s == HE_OK) s = allow_lds(k_ntt_batch<true>, ntt_lds_bytes(N, 1));
+  if (s == HE_OK && logN == 14) s = allow_lds(k_encrypt_s<14>, static_lds_bytes(14, 2));
+  if (s == HE_OK && logN == 14) s = allow_lds(k_decrypt_s<14>, static_lds_bytes(14, 1));
+  if (s == HE_OK && logN == 14) s = allow_lds(k_ntt_batch_s<14, false>, static_lds_bytes(14, 1));
+  if (s == HE_OK && logN == 14) s = allow_lds(k_ntt_batch_s<14, true>, static_lds_bytes(14, 1));
+  if (s == HE_OK && logN == 13) s = allow_lds(k_encrypt_s<13>, static_lds_bytes(13, 2));
+  if (s == HE_OK && logN == 13) s = allow_lds(k_decrypt_s<13>, static_lds_bytes(13, 1));
+  if (s == HE_OK && logN == 13) s = allow_lds(k_ntt_batch_s<13, false>, static_lds_bytes(13, 1));
+  if (s == HE_OK && logN == 13) s = allow_lds(k_ntt_batch_s<13, true>, static_lds_bytes(13, 1));
   if (s == HE_OK) s = allow_lds(k_decode<1>, fft_lds_bytes(n));
   if (s == HE_OK) s = allow_lds(k_decode<2>, fft_lds_bytes(n));
   if (s == HE_OK) s = allow_lds(k_decode<3>, fft_lds_bytes(n));
@@ -974,7 +1198,7 @@ he_status he_keygen(he_ctx* ctx, uint64_t seed, he_pk** pk_out, he_sk** sk_out, 
   hipLaunchKernelGGL(k_keygen_sample, g1, b1, 0, st, rg, key, sk->coeff, s_res, e_res, a_res);
   KG_TRY(hipGetLastError());
   // forward transform of all 3L polynomials: polynomial index b -> limb b % L
-  hipLaunchKernelGGL(k_ntt_batch<false>, dim3(3 * rg.L), dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 1), st, rg, -1, tmp);
+  launch_ntt_batch(rg, false, -1, tmp, 3 * rg.L, st);
   KG_TRY(hipGetLastError());
   hipLaunchKernelGGL(k_keygen_combine, g1, b1, 0, st, rg, s_res, e_res, a_res, pk->raw, pk->tab, sk->tab);
   KG_TRY(hipGetLastError());
@@ -1330,10 +1554,7 @@ he_status he_debug_ntt(he_ctx* ctx, int inverse, uint32_t limb, uint32_t* polys_
   const RingDev& rg = ctx->ring;
   hipStream_t st = static_cast<hipStream_t>(stream);
   KernelTimer timer_(ctx, KID_NTT, st);
-  if (inverse)
-    hipLaunchKernelGGL(k_ntt_batch<true>, dim3((uint32_t)batch), dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 1), st, rg, (int)limb, polys_dev);
-  else
-    hipLaunchKernelGGL(k_ntt_batch<false>, dim3((uint32_t)batch), dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 1), st, rg, (int)limb, polys_dev);
+  launch_ntt_batch(rg, inverse != 0, (int)limb, polys_dev, (uint32_t)batch, st);
   HIP_TRY(hipGetLastError());
   return HE_OK;
 }
@@ -1347,7 +1568,7 @@ he_status he_debug_export_keys(he_ctx* ctx, const he_pk* pk, const he_sk* sk, ui
   if (pk_coeff_dev) {
     if (!pk || pk->ctx != ctx) return fail(HE_ERR_INVALID_ARG, "public key missing or from another context");
     HIP_TRY(hipMemcpyAsync(pk_coeff_dev, pk->raw, 2ull * rg.L * rg.N * 4, hipMemcpyDeviceToDevice, st));
-    hipLaunchKernelGGL(k_ntt_batch<true>, dim3(2 * rg.L), dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 1), st, rg, -1, pk_coeff_dev);
+    launch_ntt_batch(rg, true, -1, pk_coeff_dev, 2 * rg.L, st);
     HIP_TRY(hipGetLastError());
   }
   if (sk_coeff_dev) {
