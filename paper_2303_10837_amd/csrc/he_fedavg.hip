@@ -13,6 +13,7 @@
 #include "he_device.hpp"
 #include "he_fedavg.h"
 #include "he_host_tables.hpp"
+#include "he_fft_static.hpp"
 #include "he_ntt_static.hpp"
 
 using namespace he;
@@ -124,6 +125,53 @@ k_encode(RingDev rg, MaskDev mk, const float* __restrict__ w, const float* __res
     out[k] = __double2int_rn(cr);
     out[k + n] = __double2int_rn(ci);
   }
+}
+
+// ---- specialised encoder: register-blocked decimation-in-time FFT, natural-order output ----
+template <int LOGN>
+__global__ void __launch_bounds__(FftPlan<LOGN - 1>::NT)
+k_encode_s(RingDev rg, MaskDev mk, const float* __restrict__ w, const float* __restrict__ slots_direct,
+           uint64_t first_ct, int32_t* __restrict__ m_out) {
+  constexpr int LOGn = LOGN - 1, n = 1 << LOGn, N = 1 << LOGN;
+  using P = FftPlan<LOGn>;
+  extern __shared__ double lds_d[];
+  double* re = lds_d;
+  double* im = lds_d + fpad(n);
+  const uint64_t c_local = blockIdx.x;
+  const uint64_t c = first_ct + c_local;
+  for (int j = threadIdx.x; j < n; j += P::NT) {
+    double z = 0.0;
+    if (slots_direct) {
+      z = (double)slots_direct[c_local * n + j];
+    } else {
+      const uint64_t t = c * (uint64_t)n + (uint64_t)j;
+      if (t < mk.P_enc) z = (double)w[run_lookup(mk.start, mk.prefix, mk.n_runs, t)];
+    }
+    re[fpad((int)rg.perm_enc[j])] = z;
+  }
+  __syncthreads();
+  const double2* e_tab = rg.fft_e;
+  auto ld_real = [=](int a, double& r, double& i) { r = re[fpad(a)]; i = 0.0; };
+  auto ldl = [=](int a, double& r, double& i) { r = re[fpad(a)]; i = im[fpad(a)]; };
+  auto stl = [=](int a, double r, double i) { re[fpad(a)] = r; im[fpad(a)] = i; };
+  fft_pass<LOGn, P::kPasses - 1, true, false>(e_tab, ld_real, stl);
+  __syncthreads();
+  if constexpr (P::kPasses == 5) {
+    fft_pass<LOGn, 3, true, false>(e_tab, ldl, stl);
+    __syncthreads();
+  }
+  fft_pass<LOGn, 2, true, false>(e_tab, ldl, stl);
+  __syncthreads();
+  fft_pass<LOGn, 1, true, false>(e_tab, ldl, stl);
+  __syncthreads();
+  const double scale = ldexp(1.0, (int)rg.scale_bits - LOGn);
+  int32_t* out = m_out + c_local * N;
+  const double2* twist = rg.twist;
+  fft_pass<LOGn, 0, true, false>(e_tab, ldl, [=](int k, double ar, double ai) {
+    const double2 tw = twist[k];
+    out[k] = __double2int_rn((ar * tw.x + ai * tw.y) * scale);
+    out[k + n] = __double2int_rn((ai * tw.x - ar * tw.y) * scale);
+  });
 }
 
 // ---- a3: ephemeral randomness of one ciphertext -----------------------------------------
@@ -498,6 +546,58 @@ k_decode(RingDev rg, CrtArgs ca, MaskDev mk, const uint32_t* __restrict__ d, uin
   }
 }
 
+// ---- specialised decoder: lift fused into the first decimation-in-frequency pass ------------
+template <int LOGN, int LEVEL>
+__global__ void __launch_bounds__(FftPlan<LOGN - 1>::NT)
+k_decode_s(RingDev rg, CrtArgs ca, MaskDev mk, const uint32_t* __restrict__ d, uint64_t first_ct,
+           float* __restrict__ w_out, double* __restrict__ slots_out) {
+  constexpr int LOGn = LOGN - 1, n = 1 << LOGn, N = 1 << LOGN;
+  using P = FftPlan<LOGn>;
+  extern __shared__ double lds_d[];
+  double* re = lds_d;
+  double* im = lds_d + fpad(n);
+  const uint64_t c_local = blockIdx.x;
+  const uint32_t* dc = d + c_local * LEVEL * N;
+  const double2* e_tab = rg.fft_e;
+  const double2* twist = rg.twist;
+  auto ldl = [=](int a, double& r, double& i) { r = re[fpad(a)]; i = im[fpad(a)]; };
+  auto stl = [=](int a, double r, double i) { re[fpad(a)] = r; im[fpad(a)] = i; };
+  fft_pass<LOGn, 0, false, true>(e_tab, [&](int k, double& r, double& i) {
+    uint32_t ra[LEVEL], rb[LEVEL];
+#pragma unroll
+    for (int j = 0; j < LEVEL; ++j) {
+      ra[j] = dc[(size_t)j * N + k];
+      rb[j] = dc[(size_t)j * N + k + n];
+    }
+    const double vr = crt_centered<LEVEL>(rg, ca, ra);
+    const double vi = crt_centered<LEVEL>(rg, ca, rb);
+    const double2 tw = twist[k];
+    r = vr * tw.x - vi * tw.y;
+    i = vr * tw.y + vi * tw.x;
+  }, stl);
+  __syncthreads();
+  fft_pass<LOGn, 1, false, true>(e_tab, ldl, stl);
+  __syncthreads();
+  fft_pass<LOGn, 2, false, true>(e_tab, ldl, stl);
+  __syncthreads();
+  fft_pass<LOGn, 3, false, true>(e_tab, ldl, stl);
+  __syncthreads();
+  if constexpr (P::kPasses == 5) {
+    fft_pass<LOGn, 4, false, true>(e_tab, ldl, stl);
+    __syncthreads();
+  }
+  const double inv_delta = ldexp(1.0, -(int)rg.scale_bits);
+  for (int j = threadIdx.x; j < n; j += P::NT) {
+    const double z = re[fpad((int)rg.perm_enc[j])] * inv_delta;  // bin t_j sits at bitrev(t_j)
+    if (slots_out) {
+      slots_out[c_local * n + j] = z;
+    } else {
+      const uint64_t t = (first_ct + c_local) * (uint64_t)n + (uint64_t)j;
+      if (t < mk.P_enc) w_out[run_lookup(mk.start, mk.prefix, mk.n_runs, t)] = (float)z;
+    }
+  }
+}
+
 // ---- plaintext remainder: compaction (client, before sending) and scatter (after) -------
 template <bool SCATTER>
 __global__ void __launch_bounds__(256)
@@ -795,6 +895,7 @@ int ntt_threads(uint32_t N) { return (int)std::min<uint32_t>(1024, std::max<uint
 int fft_threads(uint32_t n) { return (int)std::min<uint32_t>(1024, std::max<uint32_t>(64, n >> 2)); }
 size_t ntt_lds_bytes(uint32_t N, int bufs) { return (size_t)bufs * lds_pad((int)N) * sizeof(uint32_t); }
 size_t fft_lds_bytes(uint32_t n) { return (size_t)2 * n * sizeof(double); }
+size_t static_fft_lds_bytes(int logn) { return (size_t)2 * fpad(1 << logn) * sizeof(double); }
 size_t static_lds_bytes(int logN, int bufs) { return (size_t)bufs * spad(1 << logN) * sizeof(uint32_t); }
 
 // Batched standalone transform: specialised kernels for the tuned sizes, generic otherwise.
@@ -837,8 +938,15 @@ he_status launch_encode(he_ctx* ctx, const MaskDev& mk, const float* w, const fl
   const uint32_t n = ctx->ring.N / 2;
   {
     KernelTimer timer_(ctx, KID_ENCODE, st);
-    hipLaunchKernelGGL(k_encode, dim3((uint32_t)n_ct), dim3(fft_threads(n)), fft_lds_bytes(n), st, ctx->ring, mk, w, slots,
-                       first_ct, m_out);
+    if (ctx->ring.logN == 14)
+      hipLaunchKernelGGL(k_encode_s<14>, dim3((uint32_t)n_ct), dim3(FftPlan<13>::NT), static_fft_lds_bytes(13), st, ctx->ring, mk, w,
+                         slots, first_ct, m_out);
+    else if (ctx->ring.logN == 13)
+      hipLaunchKernelGGL(k_encode_s<13>, dim3((uint32_t)n_ct), dim3(FftPlan<12>::NT), static_fft_lds_bytes(12), st, ctx->ring, mk, w,
+                         slots, first_ct, m_out);
+    else
+      hipLaunchKernelGGL(k_encode, dim3((uint32_t)n_ct), dim3(fft_threads(n)), fft_lds_bytes(n), st, ctx->ring, mk, w, slots,
+                         first_ct, m_out);
   }
   HIP_TRY(hipGetLastError());
   return HE_OK;
@@ -889,8 +997,15 @@ template <int LEVEL>
 void launch_decode_t(he_ctx* ctx, const CrtArgs& ca, const MaskDev& mk, const uint32_t* d, uint64_t first_ct, uint64_t n_ct,
                      float* w_out, double* slots_out, hipStream_t st) {
   const uint32_t n = ctx->ring.N / 2;
-  hipLaunchKernelGGL(k_decode<LEVEL>, dim3((uint32_t)n_ct), dim3(fft_threads(n)), fft_lds_bytes(n), st, ctx->ring, ca, mk, d,
-                     first_ct, w_out, slots_out);
+  if (ctx->ring.logN == 14)
+    hipLaunchKernelGGL((k_decode_s<14, LEVEL>), dim3((uint32_t)n_ct), dim3(FftPlan<13>::NT), static_fft_lds_bytes(13), st, ctx->ring,
+                       ca, mk, d, first_ct, w_out, slots_out);
+  else if (ctx->ring.logN == 13)
+    hipLaunchKernelGGL((k_decode_s<13, LEVEL>), dim3((uint32_t)n_ct), dim3(FftPlan<12>::NT), static_fft_lds_bytes(12), st, ctx->ring,
+                       ca, mk, d, first_ct, w_out, slots_out);
+  else
+    hipLaunchKernelGGL(k_decode<LEVEL>, dim3((uint32_t)n_ct), dim3(fft_threads(n)), fft_lds_bytes(n), st, ctx->ring, ca, mk, d,
+                       first_ct, w_out, slots_out);
 }
 
 he_status launch_decode(he_ctx* ctx, uint32_t level, const MaskDev& mk, const uint32_t* d, uint64_t first_ct, uint64_t n_ct,
@@ -1117,6 +1232,24 @@ he_status he_ctx_create(const he_params* params, int device, he_ctx** out) {
   if (s == HE_OK && logN == 13) s = allow_lds(k_decrypt_s<13>, static_lds_bytes(13, 1));
   if (s == HE_OK && logN == 13) s = allow_lds(k_ntt_batch_s<13, false>, static_lds_bytes(13, 1));
   if (s == HE_OK && logN == 13) s = allow_lds(k_ntt_batch_s<13, true>, static_lds_bytes(13, 1));
+  if (s == HE_OK && logN == 14) s = allow_lds(k_encode_s<14>, static_fft_lds_bytes(13));
+  if (s == HE_OK && logN == 14) s = allow_lds(k_decode_s<14, 1>, static_fft_lds_bytes(13));
+  if (s == HE_OK && logN == 14) s = allow_lds(k_decode_s<14, 2>, static_fft_lds_bytes(13));
+  if (s == HE_OK && logN == 14) s = allow_lds(k_decode_s<14, 3>, static_fft_lds_bytes(13));
+  if (s == HE_OK && logN == 14) s = allow_lds(k_decode_s<14, 4>, static_fft_lds_bytes(13));
+  if (s == HE_OK && logN == 14) s = allow_lds(k_decode_s<14, 5>, static_fft_lds_bytes(13));
+  if (s == HE_OK && logN == 14) s = allow_lds(k_decode_s<14, 6>, static_fft_lds_bytes(13));
+  if (s == HE_OK && logN == 14) s = allow_lds(k_decode_s<14, 7>, static_fft_lds_bytes(13));
+  if (s == HE_OK && logN == 14) s = allow_lds(k_decode_s<14, 8>, static_fft_lds_bytes(13));
+  if (s == HE_OK && logN == 13) s = allow_lds(k_encode_s<13>, static_fft_lds_bytes(12));
+  if (s == HE_OK && logN == 13) s = allow_lds(k_decode_s<13, 1>, static_fft_lds_bytes(12));
+  if (s == HE_OK && logN == 13) s = allow_lds(k_decode_s<13, 2>, static_fft_lds_bytes(12));
+  if (s == HE_OK && logN == 13) s = allow_lds(k_decode_s<13, 3>, static_fft_lds_bytes(12));
+  if (s == HE_OK && logN == 13) s = allow_lds(k_decode_s<13, 4>, static_fft_lds_bytes(12));
+  if (s == HE_OK && logN == 13) s = allow_lds(k_decode_s<13, 5>, static_fft_lds_bytes(12));
+  if (s == HE_OK && logN == 13) s = allow_lds(k_decode_s<13, 6>, static_fft_lds_bytes(12));
+  if (s == HE_OK && logN == 13) s = allow_lds(k_decode_s<13, 7>, static_fft_lds_bytes(12));
+  if (s == HE_OK && logN == 13) s = allow_lds(k_decode_s<13, 8>, static_fft_lds_bytes(12));
   if (s == HE_OK) s = allow_lds(k_decode<1>, fft_lds_bytes(n));
   if (s == HE_OK) s = allow_lds(k_decode<2>, fft_lds_bytes(n));
   if (s == HE_OK) s = allow_lds(k_decode<3>, fft_lds_bytes(n));
