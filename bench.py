@@ -33,6 +33,18 @@ def encrypt_ops_per_ct(N, L):
     return L * (3 * (N // 2) * log_n * OPS_BUTTERFLY + 2 * N * OPS_POINTWISE + 2 * N * OPS_FINAL_ADD)
 
 
+def measured_traffic(workload):
+    """HBM bytes per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary, if any."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"hbm_traffic_{workload}.txt")
+    out = {}
+    if os.path.exists(path):
+        for line in open(path):
+            parts = line.split()
+            if len(parts) >= 3 and parts[0] == "traffic_bytes_per_launch":
+                out[parts[1]] = float(parts[2])
+    return out
+
+
 def cpu_baseline(w, ws_host, alpha, runs, budget_s=15.0):
     """Times the CPU oracle on a bounded sample of ciphertext indices of the same workload."""
     from oracle import fedavg as ofed, scheme as osch
@@ -70,6 +82,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="resnet18_full")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (known HBM traffic, for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (ciphertext indices are independent, so more GPUs "
@@ -130,6 +144,34 @@ def main():
     ms_step = dt * 1e3 / args.steps
     phase_ms /= args.steps
 
+    # standalone transform throughput (he_debug_ntt, in place): forward then inverse over a batch
+    batch = 4096
+    polys = torch.randint(0, ctx.primes[-1], (batch, N), dtype=torch.int32, device="cuda")
+    he.he_debug_ntt(ctx, False, L - 1, polys)
+    he.he_debug_ntt(ctx, True, L - 1, polys)
+    torch.cuda.synchronize()
+    he.he_debug_timing_enable(ctx, True)
+    he.he_debug_timing_read(ctx)
+    for _ in range(5):
+        he.he_debug_ntt(ctx, False, L - 1, polys)
+        he.he_debug_ntt(ctx, True, L - 1, polys)
+    ntt_ms, ntt_launches = he.he_debug_timing_read(ctx)["ntt"]
+    he.he_debug_timing_enable(ctx, False)
+    ntt_coeff_per_s = batch * N * ntt_launches / (ntt_ms * 1e-3)
+    log_n = N.bit_length() - 1
+    ntt_tops = ntt_coeff_per_s * (log_n / 2) * OPS_BUTTERFLY / 1e12
+    roofline_ntt = {"kernel": "k_ntt_batch_s", "bound": "alu", "achieved": ntt_tops, "peak": ALU_PEAK_TOPS, "unit": "TOP/s",
+                    "frac": ntt_tops / ALU_PEAK_TOPS, "traffic": None, "avg_launch_ms": ntt_ms / ntt_launches,
+                    "launches": int(ntt_launches), "coeff_per_s": ntt_coeff_per_s,
+                    "hbm_GBps": ntt_coeff_per_s * 8 / 1e9, "hbm_frac": ntt_coeff_per_s * 8 / 1e9 / HBM_PEAK_GBS}
+    del polys
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.int32, device="cuda").fill_(1)   # 1 GiB
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # sanity: the decoded aggregate is FedAvg up to the CKKS noise (not part of the timing)
     ref = sum(float(a) * x.double() for a, x in zip(alpha, ws))
     max_err = float((out.double() - ref).abs().max())
@@ -143,12 +185,16 @@ def main():
     agg_bytes = n_ct * 2 * N * 4 * (K * L + (L - 1)) * args.steps
     agg_gbs = agg_bytes / (agg_ms * 1e-3) / 1e9 if agg_ms else 0.0
     dominant = max(kern, key=lambda k: kern[k][0])
+    traffic = measured_traffic(w.name)
     roofline = {"kernel": "k_encrypt", "bound": "alu", "achieved": enc_tops, "peak": ALU_PEAK_TOPS, "unit": "TOP/s",
-                "frac": enc_tops / ALU_PEAK_TOPS, "traffic": None,
+                "frac": enc_tops / ALU_PEAK_TOPS, "traffic": traffic.get("k_encrypt"),
                 "avg_launch_ms": enc_ms / max(enc_launches, 1), "launches": int(enc_launches),
+                "algorithmic_ops_per_launch": enc_ops / max(enc_launches, 1),
+                "algorithmic_bytes_per_launch": enc_bytes / max(enc_launches, 1),
                 "hbm_GBps": enc_bytes / (enc_ms * 1e-3) / 1e9 if enc_ms else 0.0}
     roofline_agg = {"kernel": "k_aggregate", "bound": "hbm", "achieved": agg_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": agg_gbs / HBM_PEAK_GBS, "traffic": None,
+                    "frac": agg_gbs / HBM_PEAK_GBS, "traffic": traffic.get("k_aggregate"),
+                    "algorithmic_bytes_per_launch": agg_bytes / max(agg_launches, 1),
                     "avg_launch_ms": agg_ms / max(agg_launches, 1), "launches": int(agg_launches)}
 
     res = {
@@ -165,7 +211,7 @@ def main():
                    "decrypt_params_per_s": P_enc / (phase_ms[2] * 1e-3)},
         "kernels_ms_per_step": {k: v[0] / args.steps for k, v in kern.items() if v[1]},
         "dominant_kernel": dominant,
-        "roofline": roofline, "roofline_aggregate": roofline_agg,
+        "roofline": roofline, "roofline_aggregate": roofline_agg, "roofline_ntt": roofline_ntt,
         "max_abs_err_vs_float64_fedavg": max_err,
     }
     if not args.no_cpu_baseline:

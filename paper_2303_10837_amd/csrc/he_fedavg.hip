@@ -280,15 +280,20 @@ __device__ __forceinline__ void load_key8(const uint2* __restrict__ key, int bas
 template <int LOGN>
 __global__ void __launch_bounds__(NttPlan<LOGN>::NT)
 k_encrypt_s(RingDev rg, const uint2* __restrict__ pk, const int8_t* __restrict__ u, const int32_t* __restrict__ me0,
-            const int8_t* __restrict__ e1, uint32_t* __restrict__ ct_out) {
+            const int8_t* __restrict__ e1, uint32_t* __restrict__ ct_out, uint32_t n_ct) {
   using P = NttPlan<LOGN>;
   constexpr int N = 1 << LOGN;
   extern __shared__ uint32_t lds_u[];
   uint32_t* A = lds_u;
   uint32_t* B = lds_u + spad(N);
   const uint32_t L = rg.L;
-  const uint32_t j = blockIdx.x;
-  const uint64_t c = blockIdx.y;
+  // Workgroups are dealt to the 8 XCDs round-robin by linear id; the L limb-workgroups of one
+  // ciphertext read the same u / m+e0 / e1, so they are placed on the same XCD (one L2) at
+  // consecutive slots: id = slot * 8 + xcd, slot = (c / 8) * L + limb, xcd = c % 8.
+  const uint32_t slot = blockIdx.x >> 3;
+  const uint32_t j = slot % L;
+  const uint64_t c = (uint64_t)(slot / L) * 8 + (blockIdx.x & 7);
+  if (c >= n_ct) return;  // whole workgroup leaves before any barrier
   const uint32_t q = rg.q[j];
   const uint2* twf = rg.tw_fwd + (size_t)j * N;
   const uint2* twi = rg.tw_inv + (size_t)j * N;
@@ -339,8 +344,9 @@ k_encrypt_s(RingDev rg, const uint2* __restrict__ pk, const int8_t* __restrict__
 #pragma unroll
       for (int i = 0; i < G::E; ++i) {
         const int a = g + (i << G::LSTRIDE);
-        out0[a] = add_mod(v[0][i], residue_of_signed(mc[a], q), q);
-        out1[a] = add_mod(v[1][i], residue_of_signed((int32_t)ec[a], q), q);
+        // streaming output: keep it from evicting the key / twiddle tables that every workgroup shares
+        __builtin_nontemporal_store(add_mod(v[0][i], residue_of_signed(mc[a], q), q), out0 + a);
+        __builtin_nontemporal_store(add_mod(v[1][i], residue_of_signed((int32_t)ec[a], q), q), out1 + a);
       }
     }
   }
@@ -620,6 +626,20 @@ __device__ __forceinline__ uint32_t reduce64(uint64_t x, uint2 c32, uint32_t q) 
   return add_mod(t, csub(csub(lo, q), q), q);        // lo < 2^32 < 3q
 }
 
+// Ciphertext streams are touched exactly once: mark them non-temporal so they do not displace
+// what other kernels keep in L2.
+__device__ __forceinline__ uint4 stream_load(const uint4* p) {
+  typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+  const v4u t = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(p));
+  return make_uint4(t.x, t.y, t.z, t.w);
+}
+__device__ __forceinline__ void stream_store(uint4* p, uint4 v) {
+  typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+  v4u t;
+  t.x = v.x; t.y = v.y; t.z = v.z; t.w = v.w;
+  __builtin_nontemporal_store(t, reinterpret_cast<v4u*>(p));
+}
+
 template <int L, bool HAS_ACC, bool FINAL>
 __global__ void __launch_bounds__(256)
 k_aggregate(AggArgs a, AggConst k, uint32_t log_n4, uint64_t n_vec, const uint4* __restrict__ acc_in,
@@ -639,7 +659,7 @@ k_aggregate(AggArgs a, AggConst k, uint32_t log_n4, uint64_t n_vec, const uint4*
       acc[0] = v.x; acc[1] = v.y; acc[2] = v.z; acc[3] = v.w;
     }
     for (uint32_t i = 0; i < a.K; ++i) {
-      const uint4 x = reinterpret_cast<const uint4*>(a.ct[i])[off];
+      const uint4 x = stream_load(reinterpret_cast<const uint4*>(a.ct[i]) + off);
       const uint64_t w = a.w[i][j];
       acc[0] += w * x.x; acc[1] += w * x.y; acc[2] += w * x.z; acc[3] += w * x.w;
       if ((i & 3) == 3) {
@@ -662,7 +682,7 @@ k_aggregate(AggArgs a, AggConst k, uint32_t log_n4, uint64_t n_vec, const uint4*
         const uint32_t rj = r > k.half_last ? r + k.qdiff[j] : r;  // centred residue, reduced mod q_j
         o[e] = mul_shoup(sub_mod(res[j][e], rj, q), k.qlinv[j], q);
       }
-      out[((cp * (L - 1) + j) << log_n4) + kk] = make_uint4(o[0], o[1], o[2], o[3]);
+      stream_store(out + (((cp * (L - 1) + j) << log_n4) + kk), make_uint4(o[0], o[1], o[2], o[3]));
     }
   }
 }
@@ -965,10 +985,13 @@ he_status launch_sample_encrypt(he_ctx* ctx, const he_pk* pk, uint64_t seed, uin
   {
     KernelTimer timer_(ctx, KID_ENCRYPT, st);
     const dim3 grid(rg.L, (uint32_t)n_ct);
+    const dim3 grid_x((uint32_t)((n_ct + 7) / 8) * 8 * rg.L);  // XCD-aware linear grid, see k_encrypt_s
     if (rg.logN == 14)
-      hipLaunchKernelGGL(k_encrypt_s<14>, grid, dim3(NttPlan<14>::NT), static_lds_bytes(14, 2), st, rg, pk->tab, u, me0, e1, ct_out);
+      hipLaunchKernelGGL(k_encrypt_s<14>, grid_x, dim3(NttPlan<14>::NT), static_lds_bytes(14, 2), st, rg, pk->tab, u, me0, e1, ct_out,
+                         (uint32_t)n_ct);
     else if (rg.logN == 13)
-      hipLaunchKernelGGL(k_encrypt_s<13>, grid, dim3(NttPlan<13>::NT), static_lds_bytes(13, 2), st, rg, pk->tab, u, me0, e1, ct_out);
+      hipLaunchKernelGGL(k_encrypt_s<13>, grid_x, dim3(NttPlan<13>::NT), static_lds_bytes(13, 2), st, rg, pk->tab, u, me0, e1, ct_out,
+                         (uint32_t)n_ct);
     else
       hipLaunchKernelGGL(k_encrypt, grid, dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 2), st, rg, pk->tab, u, me0, e1, ct_out);
   }
