@@ -89,6 +89,26 @@ __device__ __forceinline__ uint64_t run_lookup(const uint64_t* __restrict__ star
   return start[lo] + (t - prefix[lo]);
 }
 
+// Index of the run that holds packed position t (prefix[r] <= t < prefix[r+1]).
+__device__ __forceinline__ uint32_t run_find(const uint64_t* __restrict__ prefix, uint32_t n_runs, uint64_t t) {
+  uint32_t lo = 0, hi = n_runs;
+  while (hi - lo > 1) {
+    const uint32_t mid = (lo + hi) >> 1;
+    if (prefix[mid] <= t) lo = mid;
+    else hi = mid;
+  }
+  return lo;
+}
+
+// Lookup when the run is known to lie in [lo, hi] (a workgroup's positions span few runs: the
+// bounds are found once per workgroup with uniform loads, the walk here is 0-2 steps).
+__device__ __forceinline__ uint64_t run_lookup_in(const uint64_t* __restrict__ start, const uint64_t* __restrict__ prefix,
+                                                  uint32_t lo, uint32_t hi, uint64_t t) {
+  uint32_t r = lo;
+  while (r < hi && prefix[r + 1] <= t) ++r;
+  return start[r] + (t - prefix[r]);
+}
+
 // ---- a1 + a2: gather under the mask and encode one ciphertext's slots -------------------
 // m_k + i m_{k+n} = Delta * zeta^-k * (1/n) * sum_j z_j exp(-2 pi i t_j k / n)
 __global__ void __launch_bounds__(1024)
@@ -139,13 +159,18 @@ k_encode_s(RingDev rg, MaskDev mk, const float* __restrict__ w, const float* __r
   double* im = lds_d + fpad(n);
   const uint64_t c_local = blockIdx.x;
   const uint64_t c = first_ct + c_local;
+  uint32_t r_lo = 0, r_hi = 0;
+  if (!slots_direct) {  // runs that this ciphertext's packed range [c*n, (c+1)*n) touches
+    r_lo = run_find(mk.prefix, mk.n_runs, c * (uint64_t)n);
+    r_hi = run_find(mk.prefix, mk.n_runs, min((c + 1) * (uint64_t)n, mk.P_enc) - 1);
+  }
   for (int j = threadIdx.x; j < n; j += P::NT) {
     double z = 0.0;
     if (slots_direct) {
       z = (double)slots_direct[c_local * n + j];
     } else {
       const uint64_t t = c * (uint64_t)n + (uint64_t)j;
-      if (t < mk.P_enc) z = (double)w[run_lookup(mk.start, mk.prefix, mk.n_runs, t)];
+      if (t < mk.P_enc) z = (double)w[run_lookup_in(mk.start, mk.prefix, r_lo, r_hi, t)];
     }
     re[fpad((int)rg.perm_enc[j])] = z;
   }
@@ -593,28 +618,76 @@ k_decode_s(RingDev rg, CrtArgs ca, MaskDev mk, const uint32_t* __restrict__ d, u
     __syncthreads();
   }
   const double inv_delta = ldexp(1.0, -(int)rg.scale_bits);
+  uint32_t r_lo = 0, r_hi = 0;
+  const uint64_t c = first_ct + c_local;
+  if (!slots_out) {
+    r_lo = run_find(mk.prefix, mk.n_runs, c * (uint64_t)n);
+    r_hi = run_find(mk.prefix, mk.n_runs, min((c + 1) * (uint64_t)n, mk.P_enc) - 1);
+  }
   for (int j = threadIdx.x; j < n; j += P::NT) {
     const double z = re[fpad((int)rg.perm_enc[j])] * inv_delta;  // bin t_j sits at bitrev(t_j)
     if (slots_out) {
       slots_out[c_local * n + j] = z;
     } else {
-      const uint64_t t = (first_ct + c_local) * (uint64_t)n + (uint64_t)j;
-      if (t < mk.P_enc) w_out[run_lookup(mk.start, mk.prefix, mk.n_runs, t)] = (float)z;
+      const uint64_t t = c * (uint64_t)n + (uint64_t)j;
+      if (t < mk.P_enc) w_out[run_lookup_in(mk.start, mk.prefix, r_lo, r_hi, t)] = (float)z;
     }
   }
 }
 
 // ---- plaintext remainder: compaction (client, before sending) and scatter (after) -------
-template <bool SCATTER>
+// A workgroup moves kMoveChunk consecutive compacted positions; lanes take consecutive positions
+// so both sides are unit-stride streams inside a run.
+constexpr uint32_t kMoveChunk = 256 * 16;
+typedef float v4f_a16 __attribute__((ext_vector_type(4)));               // 16-byte aligned
+typedef float v4f_a4 __attribute__((ext_vector_type(4), aligned(4)));    // element-aligned only
+
+// VEC: the compacted buffer is 16-byte aligned, so a thread moves 4 consecutive compacted
+// positions with one 16-byte access on each side when they fall into one run (the model side
+// is then only 4-byte aligned, which the hardware's unaligned access mode handles).
+template <bool SCATTER, bool VEC>
 __global__ void __launch_bounds__(256)
 k_plain_move(MaskDev mk, const float* __restrict__ src, float* __restrict__ dst) {
   const uint64_t n_plain = mk.P - mk.P_enc;
-  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
-  for (uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; t < n_plain; t += stride) {
-    const uint64_t idx = run_lookup(mk.cstart, mk.cprefix, mk.n_cruns, t);
-    if (SCATTER) dst[idx] = src[t];
-    else dst[t] = src[idx];
+  const uint64_t t0 = (uint64_t)blockIdx.x * kMoveChunk;
+  const uint64_t t1 = min(t0 + kMoveChunk, n_plain);
+  if (t0 >= t1) return;
+  const uint32_t lo = run_find(mk.cprefix, mk.n_cruns, t0);
+  const uint32_t hi = run_find(mk.cprefix, mk.n_cruns, t1 - 1);
+  if (VEC) {
+#pragma unroll 4
+    for (uint64_t t = t0 + 4 * (uint64_t)threadIdx.x; t < t1; t += 4 * 256) {
+      uint32_t r = lo;
+      while (r < hi && mk.cprefix[r + 1] <= t) ++r;
+      const uint64_t idx = mk.cstart[r] + (t - mk.cprefix[r]);
+      if (t + 4 <= t1 && t + 4 <= mk.cprefix[r + 1]) {  // 4 positions, one run
+        if (SCATTER) *reinterpret_cast<v4f_a4*>(dst + idx) = __builtin_nontemporal_load(reinterpret_cast<const v4f_a16*>(src + t));
+        else __builtin_nontemporal_store(*reinterpret_cast<const v4f_a4*>(src + idx), reinterpret_cast<v4f_a16*>(dst + t));
+      } else {
+        for (uint64_t e = t; e < min(t + 4, t1); ++e) {
+          const uint64_t ie = run_lookup_in(mk.cstart, mk.cprefix, r, hi, e);
+          if (SCATTER) dst[ie] = src[e];
+          else dst[e] = src[ie];
+        }
+      }
+    }
+  } else {
+#pragma unroll 4
+    for (uint64_t t = t0 + threadIdx.x; t < t1; t += 256) {
+      const uint64_t idx = run_lookup_in(mk.cstart, mk.cprefix, lo, hi, t);
+      if (SCATTER) dst[idx] = src[t];
+      else dst[t] = src[idx];
+    }
   }
+}
+
+template <bool SCATTER>
+void launch_plain_move(const MaskDev& mk, const float* src, float* dst, hipStream_t st) {
+  const uint64_t n_plain = mk.P - mk.P_enc;
+  const dim3 grid((uint32_t)((n_plain + kMoveChunk - 1) / kMoveChunk)), block(256);
+  const bool aligned = reinterpret_cast<uintptr_t>(SCATTER ? (const void*)src : (const void*)dst) % 16 == 0;
+  if (aligned) hipLaunchKernelGGL((k_plain_move<SCATTER, true>), grid, block, 0, st, mk, src, dst);
+  else hipLaunchKernelGGL((k_plain_move<SCATTER, false>), grid, block, 0, st, mk, src, dst);
 }
 
 // ---- a5 + a6: sum_i w_i ct_i (mod q_j) over clients, then rescale by q_{L-1} ---------------
@@ -689,22 +762,41 @@ k_aggregate(AggArgs a, AggConst k, uint32_t log_n4, uint64_t n_vec, const uint4*
 
 // ---- a7: plain FedAvg of the unmasked remainder -------------------------------------------
 // acc <- acc + alpha_i * w_i in float64, product and sum rounded separately, client order.
-template <bool HAS_ACC, bool FINAL>
+// VEC = 4: one thread owns 4 consecutive parameters (16-byte loads; all client pointers and
+// the outputs must be 16-byte aligned); the tail and unaligned calls use VEC = 1.
+template <bool HAS_ACC, bool FINAL, int VEC>
 __global__ void __launch_bounds__(256)
-k_plain_fedavg(PlainArgs a, uint64_t n_plain, const double* __restrict__ acc_in, double* __restrict__ acc_out,
-               float* __restrict__ out) {
+k_plain_fedavg(PlainArgs a, uint64_t first, uint64_t n_groups, const double* __restrict__ acc_in,
+               double* __restrict__ acc_out, float* __restrict__ out) {
   // The product and the sum must round separately (no fused multiply-add), or the result
   // depends on the compiler's contraction choices.
 #pragma clang fp contract(off)
-  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
-  for (uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; t < n_plain; t += stride) {
-    double acc = HAS_ACC ? acc_in[t] : 0.0;
-    for (uint32_t i = 0; i < a.K; ++i) {
-      const double prod = a.alpha[i] * (double)a.w[i][t];
-      acc = acc + prod;
+  const uint64_t g = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (g >= n_groups) return;
+  const uint64_t t = first + g * VEC;
+  double acc[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) acc[e] = HAS_ACC ? acc_in[t + e] : 0.0;
+  for (uint32_t i = 0; i < a.K; ++i) {
+    const double al = a.alpha[i];
+    float x[VEC];
+    if (VEC == 4) {
+      typedef float v4f __attribute__((ext_vector_type(4)));
+      const v4f v = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(a.w[i] + t));
+      x[0] = v.x; x[1 % VEC] = v.y; x[2 % VEC] = v.z; x[3 % VEC] = v.w;
+    } else {
+      x[0] = a.w[i][t];
     }
-    if (FINAL) out[t] = (float)acc;
-    else acc_out[t] = acc;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      const double prod = al * (double)x[e];
+      acc[e] = acc[e] + prod;
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) {
+    if (FINAL) out[t + e] = (float)acc[e];
+    else acc_out[t + e] = acc[e];
   }
 }
 
@@ -1089,15 +1181,27 @@ he_status launch_agg(he_ctx* ctx, bool has_acc, bool fin, const AggArgs& a, uint
   return HE_OK;
 }
 
+template <int VEC>
+void launch_plain_v(bool has_acc, bool fin, const PlainArgs& a, uint64_t first, uint64_t n_groups, const double* acc_in,
+                    double* acc_out, float* out, hipStream_t st) {
+  if (n_groups == 0) return;
+  const dim3 grid((uint32_t)((n_groups + 255) / 256)), block(256);
+  if (has_acc && fin) hipLaunchKernelGGL((k_plain_fedavg<true, true, VEC>), grid, block, 0, st, a, first, n_groups, acc_in, acc_out, out);
+  else if (has_acc) hipLaunchKernelGGL((k_plain_fedavg<true, false, VEC>), grid, block, 0, st, a, first, n_groups, acc_in, acc_out, out);
+  else if (fin) hipLaunchKernelGGL((k_plain_fedavg<false, true, VEC>), grid, block, 0, st, a, first, n_groups, acc_in, acc_out, out);
+  else hipLaunchKernelGGL((k_plain_fedavg<false, false, VEC>), grid, block, 0, st, a, first, n_groups, acc_in, acc_out, out);
+}
+
 he_status launch_plain(he_ctx* ctx, bool has_acc, bool fin, const PlainArgs& a, uint64_t n_plain, const double* acc_in,
                        double* acc_out, float* out, hipStream_t st) {
   if (n_plain == 0) return HE_OK;
-  const dim3 grid(grid_for(n_plain, 256)), block(256);
+  if (n_plain > (1ull << 40)) return fail(HE_ERR_INVALID_ARG, "plaintext part too long for one launch");
+  bool aligned = (reinterpret_cast<uintptr_t>(acc_in) | reinterpret_cast<uintptr_t>(acc_out) | reinterpret_cast<uintptr_t>(out)) % 16 == 0;
+  for (uint32_t i = 0; i < a.K; ++i) aligned = aligned && reinterpret_cast<uintptr_t>(a.w[i]) % 16 == 0;
+  const uint64_t n_vec = aligned ? n_plain / 4 : 0;
   KernelTimer timer_(ctx, KID_PLAIN_FEDAVG, st);
-  if (has_acc && fin) hipLaunchKernelGGL((k_plain_fedavg<true, true>), grid, block, 0, st, a, n_plain, acc_in, acc_out, out);
-  else if (has_acc) hipLaunchKernelGGL((k_plain_fedavg<true, false>), grid, block, 0, st, a, n_plain, acc_in, acc_out, out);
-  else if (fin) hipLaunchKernelGGL((k_plain_fedavg<false, true>), grid, block, 0, st, a, n_plain, acc_in, acc_out, out);
-  else hipLaunchKernelGGL((k_plain_fedavg<false, false>), grid, block, 0, st, a, n_plain, acc_in, acc_out, out);
+  launch_plain_v<4>(has_acc, fin, a, 0, n_vec, acc_in, acc_out, out, st);
+  launch_plain_v<1>(has_acc, fin, a, n_vec * 4, n_plain - n_vec * 4, acc_in, acc_out, out, st);
   HIP_TRY(hipGetLastError());
   return HE_OK;
 }
@@ -1511,7 +1615,7 @@ he_status he_encrypt_masked(he_ctx* ctx, const he_pk* pk, const he_mask* mask, u
   }
   if (n_plain) {
     KernelTimer timer_(ctx, KID_PLAIN_MOVE, st);
-    hipLaunchKernelGGL(k_plain_move<false>, dim3(grid_for(n_plain, 256, 1u << 16)), dim3(256), 0, st, mk, w_dev, plain_out_dev);
+    launch_plain_move<false>(mk, w_dev, plain_out_dev, st);
     HIP_TRY(hipGetLastError());
   }
   return HE_OK;
@@ -1626,7 +1730,7 @@ he_status he_decrypt_merge(he_ctx* ctx, const he_sk* sk, const he_mask* mask, co
   }
   if (n_plain) {
     KernelTimer timer_(ctx, KID_PLAIN_MOVE, st);
-    hipLaunchKernelGGL(k_plain_move<true>, dim3(grid_for(n_plain, 256, 1u << 16)), dim3(256), 0, st, mk, plain_glob_dev, w_out_dev);
+    launch_plain_move<true>(mk, plain_glob_dev, w_out_dev, st);
     HIP_TRY(hipGetLastError());
   }
   return HE_OK;
