@@ -172,13 +172,13 @@ k_encode_s(RingDev rg, MaskDev mk, const float* __restrict__ w, const float* __r
       const uint64_t t = c * (uint64_t)n + (uint64_t)j;
       if (t < mk.P_enc) z = (double)w[run_lookup_in(mk.start, mk.prefix, r_lo, r_hi, t)];
     }
-    re[fpad((int)rg.perm_enc[j])] = z;
+    re[fswz<LOGn>((int)rg.perm_enc[j])] = z;
   }
   __syncthreads();
   const double2* e_tab = rg.fft_e;
-  auto ld_real = [=](int a, double& r, double& i) { r = re[fpad(a)]; i = 0.0; };
-  auto ldl = [=](int a, double& r, double& i) { r = re[fpad(a)]; i = im[fpad(a)]; };
-  auto stl = [=](int a, double r, double i) { re[fpad(a)] = r; im[fpad(a)] = i; };
+  auto ld_real = [=](int a, double& r, double& i) { r = re[fswz<LOGn>(a)]; i = 0.0; };
+  auto ldl = [=](int a, double& r, double& i) { r = re[fswz<LOGn>(a)]; i = im[fswz<LOGn>(a)]; };
+  auto stl = [=](int a, double r, double i) { re[fswz<LOGn>(a)] = r; im[fswz<LOGn>(a)] = i; };
   fft_pass<LOGn, P::kPasses - 1, true, false>(e_tab, ld_real, stl);
   __syncthreads();
   if constexpr (P::kPasses == 5) {
@@ -591,8 +591,8 @@ k_decode_s(RingDev rg, CrtArgs ca, MaskDev mk, const uint32_t* __restrict__ d, u
   const uint32_t* dc = d + c_local * LEVEL * N;
   const double2* e_tab = rg.fft_e;
   const double2* twist = rg.twist;
-  auto ldl = [=](int a, double& r, double& i) { r = re[fpad(a)]; i = im[fpad(a)]; };
-  auto stl = [=](int a, double r, double i) { re[fpad(a)] = r; im[fpad(a)] = i; };
+  auto ldl = [=](int a, double& r, double& i) { r = re[fswz<LOGn>(a)]; i = im[fswz<LOGn>(a)]; };
+  auto stl = [=](int a, double r, double i) { re[fswz<LOGn>(a)] = r; im[fswz<LOGn>(a)] = i; };
   fft_pass<LOGn, 0, false, true>(e_tab, [&](int k, double& r, double& i) {
     uint32_t ra[LEVEL], rb[LEVEL];
 #pragma unroll
@@ -625,7 +625,7 @@ k_decode_s(RingDev rg, CrtArgs ca, MaskDev mk, const uint32_t* __restrict__ d, u
     r_hi = run_find(mk.prefix, mk.n_runs, min((c + 1) * (uint64_t)n, mk.P_enc) - 1);
   }
   for (int j = threadIdx.x; j < n; j += P::NT) {
-    const double z = re[fpad((int)rg.perm_enc[j])] * inv_delta;  // bin t_j sits at bitrev(t_j)
+    const double z = re[fswz<LOGn>((int)rg.perm_enc[j])] * inv_delta;  // bin t_j sits at bitrev(t_j)
     if (slots_out) {
       slots_out[c_local * n + j] = z;
     } else {

@@ -7,14 +7,24 @@
 // values per group and pass.
 //   decimation in frequency (natural in, bit-reversed out): passes in plan order;
 //   decimation in time      (bit-reversed in, natural out): passes in reverse order.
-// Index padding: one extra element per 8 keeps the contiguous pass and the stride-8 pass on
-// distinct banks.
+// LDS layout: no padding but an XOR swizzle of the low five index bits (the bank of an 8-byte
+// element).  With lanes taking the lowest index bits that a pass leaves free, the 32 lanes of a
+// half-wave vary index bits {0..4} in the wide-stride passes, {0,1,2} plus two higher bits in
+// the stride-8 pass and {3..7} in the contiguous pass; the swizzle below makes the map from
+// each of those bit sets to the five bank bits one-to-one (full rank over GF(2)).
+//   n = 8192 (passes over bits 12-10, 9-7, 6-5, 4-3, 2-0): b5 -> x0^x3, b6 -> x1^x4, b7 -> x2
+//   n = 4096 (passes over bits 11-9, 8-6, 5-3, 2-0):       b5 -> x0, b6 -> x1^x3, b7 -> x2^x4
 #pragma once
 #include "he_ntt_static.hpp"
 
 namespace he {
 
-__host__ __device__ __forceinline__ constexpr int fpad(int a) { return a + (a >> 3); }
+template <int LOGn>
+__host__ __device__ __forceinline__ constexpr int fswz(int a) {
+  const int t = (a >> 5) & 7;
+  return LOGn == 13 ? (a ^ t ^ ((t & 3) << 3)) : (a ^ t ^ ((t & 6) << 2));
+}
+__host__ __device__ __forceinline__ constexpr int fpad(int a) { return a; }  // array extent
 
 template <int LOGn>
 struct FftPlan;
