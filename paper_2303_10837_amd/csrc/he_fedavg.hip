@@ -34,6 +34,7 @@ struct RingDev {
   const double2* twist;      // [n]     exp(+i pi k / N)
   const uint32_t* perm_enc;  // [n]     bitrev(t_j): where slot j enters the encoder FFT
   const uint32_t* perm_dec;  // [n]     t_j: where slot j leaves the decoder FFT
+  const uint32_t* perm_half; // [n]     (bitrev_{log2(n)-1}(t_j >> 1) << 1) | (t_j & 1): half-length encoder input
   const uint2* garner_inv;   // [kMaxLimbs * kMaxLimbs]: entry i*kMaxLimbs+j = q_i^-1 mod q_j, i < j
 };
 
@@ -147,16 +148,20 @@ k_encode(RingDev rg, MaskDev mk, const float* __restrict__ w, const float* __res
   }
 }
 
-// ---- specialised encoder: register-blocked decimation-in-time FFT, natural-order output ----
+// ---- specialised encoder: the slot vector is real, so its n-point transform comes from one
+// n/2-point complex FFT of z_s = Y_{2s} + i Y_{2s+1} (Y = slots placed at their bins) and a
+// split step:  E_k = (Z_k + conj Z_{h-k})/2,  O_k = (Z_k - conj Z_{h-k})/(2i),
+//              A_k = E_k + w^k O_k,  A_{k+h} = E_k - w^k O_k,  w = exp(-2 pi i / n),  h = n/2.
+// Half the flops and half the LDS (two workgroups per CU) of the full-length transform.
 template <int LOGN>
-__global__ void __launch_bounds__(FftPlan<LOGN - 1>::NT)
-k_encode_s(RingDev rg, MaskDev mk, const float* __restrict__ w, const float* __restrict__ slots_direct,
+__global__ void __launch_bounds__(FftPlan<LOGN - 2>::NT)
+k_encode_r(RingDev rg, MaskDev mk, const float* __restrict__ w, const float* __restrict__ slots_direct,
            uint64_t first_ct, int32_t* __restrict__ m_out) {
-  constexpr int LOGn = LOGN - 1, n = 1 << LOGn, N = 1 << LOGN;
-  using P = FftPlan<LOGn>;
+  constexpr int LOGh = LOGN - 2, h = 1 << LOGh, n = 2 * h, N = 4 * h;
+  using P = FftPlan<LOGh>;
   extern __shared__ double lds_d[];
   double* re = lds_d;
-  double* im = lds_d + fpad(n);
+  double* im = lds_d + h;
   const uint64_t c_local = blockIdx.x;
   const uint64_t c = first_ct + c_local;
   uint32_t r_lo = 0, r_hi = 0;
@@ -172,31 +177,41 @@ k_encode_s(RingDev rg, MaskDev mk, const float* __restrict__ w, const float* __r
       const uint64_t t = c * (uint64_t)n + (uint64_t)j;
       if (t < mk.P_enc) z = (double)w[run_lookup_in(mk.start, mk.prefix, r_lo, r_hi, t)];
     }
-    re[fswz<LOGn>((int)rg.perm_enc[j])] = z;
+    const uint32_t code = rg.perm_half[j];  // (bitrev(bin >> 1) << 1) | (bin & 1)
+    ((code & 1) ? im : re)[fswz<LOGh>((int)(code >> 1))] = z;
   }
   __syncthreads();
-  const double2* e_tab = rg.fft_e;
-  auto ld_real = [=](int a, double& r, double& i) { r = re[fswz<LOGn>(a)]; i = 0.0; };
-  auto ldl = [=](int a, double& r, double& i) { r = re[fswz<LOGn>(a)]; i = im[fswz<LOGn>(a)]; };
-  auto stl = [=](int a, double r, double i) { re[fswz<LOGn>(a)] = r; im[fswz<LOGn>(a)] = i; };
-  fft_pass<LOGn, P::kPasses - 1, true, false>(e_tab, ld_real, stl);
+  const double2* e_tab = rg.fft_e;  // roots of the n-point transform: the h-point one uses every other entry
+  auto ldl = [=](int a, double& r, double& i) { r = re[fswz<LOGh>(a)]; i = im[fswz<LOGh>(a)]; };
+  auto stl = [=](int a, double r, double i) { re[fswz<LOGh>(a)] = r; im[fswz<LOGh>(a)] = i; };
+  fft_pass<LOGh, 3, true, false, 1>(e_tab, ldl, stl);
   __syncthreads();
-  if constexpr (P::kPasses == 5) {
-    fft_pass<LOGn, 3, true, false>(e_tab, ldl, stl);
-    __syncthreads();
-  }
-  fft_pass<LOGn, 2, true, false>(e_tab, ldl, stl);
+  fft_pass<LOGh, 2, true, false, 1>(e_tab, ldl, stl);
   __syncthreads();
-  fft_pass<LOGn, 1, true, false>(e_tab, ldl, stl);
+  fft_pass<LOGh, 1, true, false, 1>(e_tab, ldl, stl);
   __syncthreads();
-  const double scale = ldexp(1.0, (int)rg.scale_bits - LOGn);
+  fft_pass<LOGh, 0, true, false, 1>(e_tab, ldl, stl);
+  __syncthreads();
+  static_assert(P::kPasses == 4, "plans of the half-length transforms have four passes");
+  const double scale = ldexp(1.0, (int)rg.scale_bits - LOGh - 2);  // Delta / n, and the 1/2 of the split step
   int32_t* out = m_out + c_local * N;
   const double2* twist = rg.twist;
-  fft_pass<LOGn, 0, true, false>(e_tab, ldl, [=](int k, double ar, double ai) {
-    const double2 tw = twist[k];
-    out[k] = __double2int_rn((ar * tw.x + ai * tw.y) * scale);
-    out[k + n] = __double2int_rn((ai * tw.x - ar * tw.y) * scale);
-  });
+  for (int k = threadIdx.x; k < h; k += P::NT) {
+    const int kp = (h - k) & (h - 1);
+    const double zr = re[fswz<LOGh>(k)], zi = im[fswz<LOGh>(k)];
+    const double pr = re[fswz<LOGh>(kp)], pi = im[fswz<LOGh>(kp)];
+    const double er = zr + pr, ei = zi - pi;          // 2 E_k
+    const double o_r = zi + pi, o_i = pr - zr;        // 2 O_k
+    const double2 wk = e_tab[k];
+    const double tr = o_r * wk.x - o_i * wk.y, ti = o_r * wk.y + o_i * wk.x;
+    const double a0r = er + tr, a0i = ei + ti;        // 2 A_k
+    const double a1r = er - tr, a1i = ei - ti;        // 2 A_{k+h}
+    const double2 t0 = twist[k], t1 = twist[k + h];
+    out[k] = __double2int_rn((a0r * t0.x + a0i * t0.y) * scale);
+    out[k + n] = __double2int_rn((a0i * t0.x - a0r * t0.y) * scale);
+    out[k + h] = __double2int_rn((a1r * t1.x + a1i * t1.y) * scale);
+    out[k + h + n] = __double2int_rn((a1i * t1.x - a1r * t1.y) * scale);
+  }
 }
 
 // ---- a3: ephemeral randomness of one ciphertext -----------------------------------------
@@ -1051,10 +1066,10 @@ he_status launch_encode(he_ctx* ctx, const MaskDev& mk, const float* w, const fl
   {
     KernelTimer timer_(ctx, KID_ENCODE, st);
     if (ctx->ring.logN == 14)
-      hipLaunchKernelGGL(k_encode_s<14>, dim3((uint32_t)n_ct), dim3(FftPlan<13>::NT), static_fft_lds_bytes(13), st, ctx->ring, mk, w,
+      hipLaunchKernelGGL(k_encode_r<14>, dim3((uint32_t)n_ct), dim3(FftPlan<12>::NT), static_fft_lds_bytes(12), st, ctx->ring, mk, w,
                          slots, first_ct, m_out);
     else if (ctx->ring.logN == 13)
-      hipLaunchKernelGGL(k_encode_s<13>, dim3((uint32_t)n_ct), dim3(FftPlan<12>::NT), static_fft_lds_bytes(12), st, ctx->ring, mk, w,
+      hipLaunchKernelGGL(k_encode_r<13>, dim3((uint32_t)n_ct), dim3(FftPlan<11>::NT), static_fft_lds_bytes(11), st, ctx->ring, mk, w,
                          slots, first_ct, m_out);
     else
       hipLaunchKernelGGL(k_encode, dim3((uint32_t)n_ct), dim3(fft_threads(n)), fft_lds_bytes(n), st, ctx->ring, mk, w, slots,
@@ -1330,11 +1345,12 @@ he_status he_ctx_create(const he_params* params, int device, he_ctx** out) {
     const he_host::D2 v = he_host::unit_root(k, 4ull * n);
     tws[k] = make_double2(v.x, v.y);
   }
-  std::vector<uint32_t> bins, penc(n), pdec(n);
+  std::vector<uint32_t> bins, penc(n), pdec(n), phalf(n);
   he_host::slot_bins(logN, &bins);
   for (uint32_t j = 0; j < n; ++j) {
     pdec[j] = bins[j];
     penc[j] = he_host::bitrev(bins[j], (int)logN - 1);
+    phalf[j] = (he_host::bitrev(bins[j] >> 1, (int)logN - 2) << 1) | (bins[j] & 1);
   }
 
   he_status s = HE_OK;
@@ -1344,6 +1360,7 @@ he_status he_ctx_create(const he_params* params, int device, he_ctx** out) {
   if (s == HE_OK) s = upload(ctx, tws, &rg.twist);
   if (s == HE_OK) s = upload(ctx, penc, &rg.perm_enc);
   if (s == HE_OK) s = upload(ctx, pdec, &rg.perm_dec);
+  if (s == HE_OK) s = upload(ctx, phalf, &rg.perm_half);
   if (s == HE_OK) s = upload(ctx, garner, &rg.garner_inv);
   // kernels that need more than the default dynamic LDS
   if (s == HE_OK) s = allow_lds(k_encode, fft_lds_bytes(n));
@@ -1359,7 +1376,7 @@ he_status he_ctx_create(const he_params* params, int device, he_ctx** out) {
   if (s == HE_OK && logN == 13) s = allow_lds(k_decrypt_s<13>, static_lds_bytes(13, 1));
   if (s == HE_OK && logN == 13) s = allow_lds(k_ntt_batch_s<13, false>, static_lds_bytes(13, 1));
   if (s == HE_OK && logN == 13) s = allow_lds(k_ntt_batch_s<13, true>, static_lds_bytes(13, 1));
-  if (s == HE_OK && logN == 14) s = allow_lds(k_encode_s<14>, static_fft_lds_bytes(13));
+  if (s == HE_OK && logN == 14) s = allow_lds(k_encode_r<14>, static_fft_lds_bytes(12));
   if (s == HE_OK && logN == 14) s = allow_lds(k_decode_s<14, 1>, static_fft_lds_bytes(13));
   if (s == HE_OK && logN == 14) s = allow_lds(k_decode_s<14, 2>, static_fft_lds_bytes(13));
   if (s == HE_OK && logN == 14) s = allow_lds(k_decode_s<14, 3>, static_fft_lds_bytes(13));
@@ -1368,7 +1385,7 @@ he_status he_ctx_create(const he_params* params, int device, he_ctx** out) {
   if (s == HE_OK && logN == 14) s = allow_lds(k_decode_s<14, 6>, static_fft_lds_bytes(13));
   if (s == HE_OK && logN == 14) s = allow_lds(k_decode_s<14, 7>, static_fft_lds_bytes(13));
   if (s == HE_OK && logN == 14) s = allow_lds(k_decode_s<14, 8>, static_fft_lds_bytes(13));
-  if (s == HE_OK && logN == 13) s = allow_lds(k_encode_s<13>, static_fft_lds_bytes(12));
+  if (s == HE_OK && logN == 13) s = allow_lds(k_encode_r<13>, static_fft_lds_bytes(11));
   if (s == HE_OK && logN == 13) s = allow_lds(k_decode_s<13, 1>, static_fft_lds_bytes(12));
   if (s == HE_OK && logN == 13) s = allow_lds(k_decode_s<13, 2>, static_fft_lds_bytes(12));
   if (s == HE_OK && logN == 13) s = allow_lds(k_decode_s<13, 3>, static_fft_lds_bytes(12));

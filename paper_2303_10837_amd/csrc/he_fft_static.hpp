@@ -14,6 +14,7 @@
 // each of those bit sets to the five bank bits one-to-one (full rank over GF(2)).
 //   n = 8192 (passes over bits 12-10, 9-7, 6-5, 4-3, 2-0): b5 -> x0^x3, b6 -> x1^x4, b7 -> x2
 //   n = 4096 (passes over bits 11-9, 8-6, 5-3, 2-0):       b5 -> x0, b6 -> x1^x3, b7 -> x2^x4
+//   n = 2048 (passes over bits 10-8, 7-5, 4-2, 1-0):       b5 -> x0^x2, b6 -> x1^x3, b7 -> x4
 #pragma once
 #include "he_ntt_static.hpp"
 
@@ -22,7 +23,7 @@ namespace he {
 template <int LOGn>
 __host__ __device__ __forceinline__ constexpr int fswz(int a) {
   const int t = (a >> 5) & 7;
-  return LOGn == 13 ? (a ^ t ^ ((t & 3) << 3)) : (a ^ t ^ ((t & 6) << 2));
+  return LOGn == 13 ? (a ^ t ^ ((t & 3) << 3)) : LOGn == 12 ? (a ^ t ^ ((t & 6) << 2)) : (a ^ (t & 3) ^ (t << 2));
 }
 __host__ __device__ __forceinline__ constexpr int fpad(int a) { return a; }  // array extent
 
@@ -36,6 +37,13 @@ struct FftPlan<13> {  // n = 8192: strides 1024, 128, 32, 8, 1
   static constexpr int NT = 1024;
 };
 template <>
+struct FftPlan<11> {  // n = 2048: strides 256, 32, 4, 1
+  static constexpr int kPasses = 4;
+  static constexpr int R[5] = {3, 3, 3, 2, 0};
+  static constexpr int S[5] = {0, 3, 6, 9, 11};
+  static constexpr int NT = 256;
+};
+template <>
 struct FftPlan<12> {  // n = 4096: strides 512, 64, 8, 1
   static constexpr int kPasses = 4;
   static constexpr int R[5] = {3, 3, 3, 3, 0};
@@ -45,7 +53,8 @@ struct FftPlan<12> {  // n = 4096: strides 512, 64, 8, 1
 
 // R stages on one group.  DIT = false: (a, b) -> (a + b, (a - b) w), stages ascending;
 // DIT = true: (a, b) -> (a + b w, a - b w), stages descending.  POS conjugates the twiddles.
-template <int LOGn, int S0, int R, bool DIT, bool POS>
+// TSHIFT: e_tab holds the roots of a transform 2^TSHIFT times longer (index scaled accordingly).
+template <int LOGn, int S0, int R, bool DIT, bool POS, int TSHIFT = 0>
 __device__ __forceinline__ void fft_stages(double (&xr)[1 << R], double (&xi)[1 << R], int o,
                                            const double2* __restrict__ e_tab) {
   constexpr int E = 1 << R;
@@ -58,7 +67,7 @@ __device__ __forceinline__ void fft_stages(double (&xr)[1 << R], double (&xi)[1 
     for (int i = 0; i < E; ++i) {
       if (i & half) continue;
       const int r = (o + ((i & (half - 1)) << LSTRIDE)) << (S0 + k);
-      double2 w = e_tab[r];
+      double2 w = e_tab[r << TSHIFT];
       if (POS) w.y = -w.y;
       if (!DIT) {
         const double ar = xr[i], ai = xi[i], br = xr[i + half], bi = xi[i + half];
@@ -81,7 +90,7 @@ __device__ __forceinline__ void fft_stages(double (&xr)[1 << R], double (&xi)[1 
 }
 
 // One pass with caller-supplied load / store (index = natural position in the n-point array).
-template <int LOGn, int PASS, bool DIT, bool POS, class LoadF, class StoreF>
+template <int LOGn, int PASS, bool DIT, bool POS, int TSHIFT = 0, class LoadF, class StoreF>
 __device__ __forceinline__ void fft_pass(const double2* __restrict__ e_tab, LoadF ld, StoreF st) {
   using P = FftPlan<LOGn>;
   constexpr int S0 = P::S[PASS], R = P::R[PASS];
@@ -92,7 +101,7 @@ __device__ __forceinline__ void fft_pass(const double2* __restrict__ e_tab, Load
     double xr[1 << R], xi[1 << R];
 #pragma unroll
     for (int i = 0; i < G::E; ++i) ld(base + (i << G::LSTRIDE), xr[i], xi[i]);
-    fft_stages<LOGn, S0, R, DIT, POS>(xr, xi, o, e_tab);
+    fft_stages<LOGn, S0, R, DIT, POS, TSHIFT>(xr, xi, o, e_tab);
 #pragma unroll
     for (int i = 0; i < G::E; ++i) st(base + (i << G::LSTRIDE), xr[i], xi[i]);
   }
