@@ -164,22 +164,39 @@ k_encode_r(RingDev rg, MaskDev mk, const float* __restrict__ w, const float* __r
   double* im = lds_d + h;
   const uint64_t c_local = blockIdx.x;
   const uint64_t c = first_ct + c_local;
-  uint32_t r_lo = 0, r_hi = 0;
-  if (!slots_direct) {  // runs that this ciphertext's packed range [c*n, (c+1)*n) touches
-    r_lo = run_find(mk.prefix, mk.n_runs, c * (uint64_t)n);
-    r_hi = run_find(mk.prefix, mk.n_runs, min((c + 1) * (uint64_t)n, mk.P_enc) - 1);
-  }
-  for (int j = threadIdx.x; j < n; j += P::NT) {
-    double z = 0.0;
-    if (slots_direct) {
-      z = (double)slots_direct[c_local * n + j];
+  // Gather: all loads of a thread are issued before any is consumed (U per thread, fixed).
+  constexpr int U = n / P::NT;
+  uint32_t code[U];
+  float z[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) code[u] = rg.perm_half[threadIdx.x + u * P::NT];  // (bitrev(bin >> 1) << 1) | (bin & 1)
+  if (slots_direct) {
+    const float* sc = slots_direct + c_local * n;
+#pragma unroll
+    for (int u = 0; u < U; ++u) z[u] = sc[threadIdx.x + u * P::NT];
+  } else {
+    // runs that this ciphertext's packed range [c*n, (c+1)*n) touches
+    const uint64_t t_first = c * (uint64_t)n;
+    const uint32_t r_lo = run_find(mk.prefix, mk.n_runs, t_first);
+    const uint32_t r_hi = run_find(mk.prefix, mk.n_runs, min(t_first + n, mk.P_enc) - 1);
+    if (r_lo == r_hi) {  // common case: one run, a plain shifted copy
+      const float* wc = w + (mk.start[r_lo] + (t_first - mk.prefix[r_lo]));
+      const uint64_t live = min((uint64_t)n, mk.P_enc - t_first);
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint32_t j = threadIdx.x + u * P::NT;
+        z[u] = j < live ? wc[j] : 0.f;
+      }
     } else {
-      const uint64_t t = c * (uint64_t)n + (uint64_t)j;
-      if (t < mk.P_enc) z = (double)w[run_lookup_in(mk.start, mk.prefix, r_lo, r_hi, t)];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint64_t t = t_first + threadIdx.x + u * P::NT;
+        z[u] = t < mk.P_enc ? w[run_lookup_in(mk.start, mk.prefix, r_lo, r_hi, t)] : 0.f;
+      }
     }
-    const uint32_t code = rg.perm_half[j];  // (bitrev(bin >> 1) << 1) | (bin & 1)
-    ((code & 1) ? im : re)[fswz<LOGh>((int)(code >> 1))] = z;
   }
+#pragma unroll
+  for (int u = 0; u < U; ++u) ((code[u] & 1) ? im : re)[fswz<LOGh>((int)(code[u] >> 1))] = (double)z[u];
   __syncthreads();
   const double2* e_tab = rg.fft_e;  // roots of the n-point transform: the h-point one uses every other entry
   auto ldl = [=](int a, double& r, double& i) { r = re[fswz<LOGh>(a)]; i = im[fswz<LOGh>(a)]; };
@@ -196,7 +213,9 @@ k_encode_r(RingDev rg, MaskDev mk, const float* __restrict__ w, const float* __r
   const double scale = ldexp(1.0, (int)rg.scale_bits - LOGh - 2);  // Delta / n, and the 1/2 of the split step
   int32_t* out = m_out + c_local * N;
   const double2* twist = rg.twist;
-  for (int k = threadIdx.x; k < h; k += P::NT) {
+#pragma unroll
+  for (int ku = 0; ku < h / P::NT; ++ku) {
+    const int k = threadIdx.x + ku * P::NT;
     const int kp = (h - k) & (h - 1);
     const double zr = re[fswz<LOGh>(k)], zi = im[fswz<LOGh>(k)];
     const double pr = re[fswz<LOGh>(kp)], pi = im[fswz<LOGh>(kp)];
