@@ -161,7 +161,8 @@ def main():
     log_n = N.bit_length() - 1
     ntt_tops = ntt_coeff_per_s * (log_n / 2) * OPS_BUTTERFLY / 1e12
     roofline_ntt = {"kernel": "k_ntt_batch_s", "bound": "alu", "achieved": ntt_tops, "peak": ALU_PEAK_TOPS, "unit": "TOP/s",
-                    "frac": ntt_tops / ALU_PEAK_TOPS, "traffic": None, "avg_launch_ms": ntt_ms / ntt_launches,
+                    "frac": ntt_tops / ALU_PEAK_TOPS, "traffic": measured_traffic(w.name).get("k_ntt_batch"),
+                    "algorithmic_bytes_per_launch": batch * N * 8, "avg_launch_ms": ntt_ms / ntt_launches,
                     "launches": int(ntt_launches), "coeff_per_s": ntt_coeff_per_s,
                     "hbm_GBps": ntt_coeff_per_s * 8 / 1e9, "hbm_frac": ntt_coeff_per_s * 8 / 1e9 / HBM_PEAK_GBS}
     del polys
@@ -181,7 +182,7 @@ def main():
     agg_ms, agg_launches = kern["aggregate"]
     enc_ops = encrypt_ops_per_ct(N, L) * n_ct * K * args.steps           # all launches of the timed region
     enc_tops = enc_ops / (enc_ms * 1e-3) / 1e12 if enc_ms else 0.0
-    enc_bytes = (16 * L + 6) * N * n_ct * K * args.steps                 # ct written + m+e0, u, e1 read once
+    enc_bytes = (8 * L + 6) * N * n_ct * K * args.steps                  # 2*L*N residues written + m+e0, u, e1 read once
     agg_bytes = n_ct * 2 * N * 4 * (K * L + (L - 1)) * args.steps
     agg_gbs = agg_bytes / (agg_ms * 1e-3) / 1e9 if agg_ms else 0.0
     dominant = max(kern, key=lambda k: kern[k][0])
