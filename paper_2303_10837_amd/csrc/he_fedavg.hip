@@ -148,6 +148,39 @@ k_encode(RingDev rg, MaskDev mk, const float* __restrict__ w, const float* __res
   }
 }
 
+// ---- a3: ephemeral randomness of one ciphertext -----------------------------------------
+// u (ternary), e0 and e1 (centred binomial), each as int8 [N].  Called by all NT threads of a
+// workgroup; every Philox block is drawn exactly once.
+template <int NT>
+__device__ __forceinline__ void sample_ct(const RngKey& rk, uint32_t N, uint32_t eta, int8_t* __restrict__ u_out,
+                                          int8_t* __restrict__ e0_out, int8_t* __restrict__ e1_out) {
+  const uint32_t mask = eta == 0 ? 0u : cbd_mask(eta);
+  uint32_t* u32 = reinterpret_cast<uint32_t*>(u_out);
+  uint32_t* e0w = reinterpret_cast<uint32_t*>(e0_out);
+  uint32_t* e1w = reinterpret_cast<uint32_t*>(e1_out);
+  auto pack4 = [](int a, int b, int c, int d) {
+    return (uint32_t)(uint8_t)a | ((uint32_t)(uint8_t)b << 8) | ((uint32_t)(uint8_t)c << 16) | ((uint32_t)(uint8_t)d << 24);
+  };
+  for (uint32_t b = threadIdx.x; b < N / 4; b += NT) {  // 4 coefficients per iteration and stream
+    const uint4 r = rng_block(rk, b, kTagU);
+    u32[b] = pack4(ternary_from_word(r.x), ternary_from_word(r.y), ternary_from_word(r.z), ternary_from_word(r.w));
+    const uint4 a0 = rng_block(rk, 2 * b, kTagE0), a1 = rng_block(rk, 2 * b + 1, kTagE0);
+    e0w[b] = pack4(cbd_from_words(a0.x, a0.y, mask), cbd_from_words(a0.z, a0.w, mask), cbd_from_words(a1.x, a1.y, mask),
+                   cbd_from_words(a1.z, a1.w, mask));
+    const uint4 b0 = rng_block(rk, 2 * b, kTagE1), b1 = rng_block(rk, 2 * b + 1, kTagE1);
+    e1w[b] = pack4(cbd_from_words(b0.x, b0.y, mask), cbd_from_words(b0.z, b0.w, mask), cbd_from_words(b1.x, b1.y, mask),
+                   cbd_from_words(b1.z, b1.w, mask));
+  }
+}
+
+__global__ void __launch_bounds__(256)
+k_sample(RingDev rg, uint2 key, uint32_t client, uint64_t first_ct, int8_t* __restrict__ u_out, int8_t* __restrict__ e0_out,
+         int8_t* __restrict__ e1_out) {
+  const uint64_t c_local = blockIdx.x;
+  const RngKey rk{key, (uint32_t)(first_ct + c_local), client};
+  sample_ct<256>(rk, rg.N, rg.eta, u_out + c_local * rg.N, e0_out + c_local * rg.N, e1_out + c_local * rg.N);
+}
+
 // ---- specialised encoder: the slot vector is real, so its n-point transform comes from one
 // n/2-point complex FFT of z_s = Y_{2s} + i Y_{2s+1} (Y = slots placed at their bins) and a
 // split step:  E_k = (Z_k + conj Z_{h-k})/2,  O_k = (Z_k - conj Z_{h-k})/(2i),
@@ -156,7 +189,8 @@ k_encode(RingDev rg, MaskDev mk, const float* __restrict__ w, const float* __res
 template <int LOGN>
 __global__ void __launch_bounds__(FftPlan<LOGN - 2>::NT)
 k_encode_r(RingDev rg, MaskDev mk, const float* __restrict__ w, const float* __restrict__ slots_direct,
-           uint64_t first_ct, int32_t* __restrict__ m_out) {
+           uint64_t first_ct, int32_t* __restrict__ m_out, uint2 key, uint32_t client, int8_t* __restrict__ u_out,
+           int8_t* __restrict__ e0_out, int8_t* __restrict__ e1_out) {
   constexpr int LOGh = LOGN - 2, h = 1 << LOGh, n = 2 * h, N = 4 * h;
   using P = FftPlan<LOGh>;
   extern __shared__ double lds_d[];
@@ -231,46 +265,20 @@ k_encode_r(RingDev rg, MaskDev mk, const float* __restrict__ w, const float* __r
     out[k + h] = __double2int_rn((a1r * t1.x + a1i * t1.y) * scale);
     out[k + h + n] = __double2int_rn((a1i * t1.x - a1r * t1.y) * scale);
   }
-}
-
-// ---- a3: ephemeral randomness of one ciphertext -----------------------------------------
-// u (ternary) and e1 (CBD) as int8, e0 (CBD) added to the plaintext: me0 = m + e0.
-__global__ void __launch_bounds__(256)
-k_sample(RingDev rg, uint2 key, uint32_t client, uint64_t first_ct, const int32_t* __restrict__ m_in,
-         int32_t* __restrict__ me0, int8_t* __restrict__ u_out, int8_t* __restrict__ e1_out) {
-  const uint64_t c_local = blockIdx.x;
-  const RngKey rk{key, (uint32_t)(first_ct + c_local), client};
-  const uint32_t N = rg.N;
-  const uint32_t mask = rg.eta == 0 ? 0u : cbd_mask(rg.eta);
-  uint32_t* u32 = reinterpret_cast<uint32_t*>(u_out + c_local * N);
-  uint32_t* e32 = reinterpret_cast<uint32_t*>(e1_out + c_local * N);
-  const int2* m2 = reinterpret_cast<const int2*>(m_in + c_local * N);
-  int2* o2 = reinterpret_cast<int2*>(me0 + c_local * N);
-  for (uint32_t b = threadIdx.x; b < N / 4; b += blockDim.x) {
-    const uint4 r = rng_block(rk, b, kTagU);
-    const uint32_t p = (uint32_t)(uint8_t)ternary_from_word(r.x) | ((uint32_t)(uint8_t)ternary_from_word(r.y) << 8) |
-                       ((uint32_t)(uint8_t)ternary_from_word(r.z) << 16) | ((uint32_t)(uint8_t)ternary_from_word(r.w) << 24);
-    u32[b] = p;
-    const uint4 r0 = rng_block(rk, 2 * b, kTagE1), r1 = rng_block(rk, 2 * b + 1, kTagE1);
-    const uint32_t pe = (uint32_t)(uint8_t)cbd_from_words(r0.x, r0.y, mask) | ((uint32_t)(uint8_t)cbd_from_words(r0.z, r0.w, mask) << 8) |
-                        ((uint32_t)(uint8_t)cbd_from_words(r1.x, r1.y, mask) << 16) | ((uint32_t)(uint8_t)cbd_from_words(r1.z, r1.w, mask) << 24);
-    e32[b] = pe;
-  }
-  for (uint32_t b = threadIdx.x; b < N / 2; b += blockDim.x) {
-    const uint4 r = rng_block(rk, b, kTagE0);
-    int2 m = m2[b];
-    m.x += cbd_from_words(r.x, r.y, mask);
-    m.y += cbd_from_words(r.z, r.w, mask);
-    o2[b] = m;
+  // The ciphertext's randomness is drawn here too: the encoder waits on memory most of the time,
+  // the sampler is pure integer arithmetic, and the two overlap across the resident wavefronts.
+  if (u_out) {
+    const RngKey rk{key, (uint32_t)c, client};
+    sample_ct<P::NT>(rk, N, rg.eta, u_out + c_local * N, e0_out + c_local * N, e1_out + c_local * N);
   }
 }
 
 // ---- a4: public-key encryption of one (ciphertext, limb) --------------------------------
 // c0 = INTT(b^ . NTT(u)) + (m + e0),  c1 = INTT(a^ . NTT(u)) + e1   (mod q_j)
-// pk holds b^ and a^ premultiplied by 1/N, with Shoup companions.
+// pk holds b^ and a^ premultiplied by 1/N, with Shoup companions; m + e0 must fit 32 bits.
 __global__ void __launch_bounds__(1024)
-k_encrypt(RingDev rg, const uint2* __restrict__ pk, const int8_t* __restrict__ u, const int32_t* __restrict__ me0,
-          const int8_t* __restrict__ e1, uint32_t* __restrict__ ct_out) {
+k_encrypt(RingDev rg, const uint2* __restrict__ pk, const int8_t* __restrict__ u, const int32_t* __restrict__ m,
+          const int8_t* __restrict__ e0, const int8_t* __restrict__ e1, uint32_t* __restrict__ ct_out) {
   extern __shared__ uint32_t lds_u[];
   const int logN = (int)rg.logN;
   const uint32_t N = rg.N, L = rg.L;
@@ -284,7 +292,8 @@ k_encrypt(RingDev rg, const uint2* __restrict__ pk, const int8_t* __restrict__ u
     const int v = uc[a];
     return (uint32_t)(v < 0 ? v + (int)q : v);
   });
-  const int32_t* mc = me0 + c * N;
+  const int32_t* mc = m + c * N;
+  const int8_t* e0c = e0 + c * N;
   const int8_t* ec = e1 + c * N;
   for (uint32_t p = 0; p < 2; ++p) {
     const uint2* key = pk + ((size_t)p * L + j) * N;
@@ -292,7 +301,7 @@ k_encrypt(RingDev rg, const uint2* __restrict__ pk, const int8_t* __restrict__ u
     if (p == 0) {
       ntt_inverse_from(
           bufW, logN, rg.tw_inv + (size_t)j * N, q, [=](int a) { return mul_shoup(bufU[lds_pad(a)], key[a], q); },
-          [=](int a, uint32_t v) { out[a] = add_mod(v, residue_of_signed(mc[a], q), q); });
+          [=](int a, uint32_t v) { out[a] = add_mod(v, residue_of_signed(mc[a] + (int32_t)e0c[a], q), q); });
     } else {
       ntt_inverse_from(
           bufW, logN, rg.tw_inv + (size_t)j * N, q, [=](int a) { return mul_shoup(bufU[lds_pad(a)], key[a], q); },
@@ -338,8 +347,8 @@ __device__ __forceinline__ void load_key8(const uint2* __restrict__ key, int bas
 
 template <int LOGN>
 __global__ void __launch_bounds__(NttPlan<LOGN>::NT)
-k_encrypt_s(RingDev rg, const uint2* __restrict__ pk, const int8_t* __restrict__ u, const int32_t* __restrict__ me0,
-            const int8_t* __restrict__ e1, uint32_t* __restrict__ ct_out, uint32_t n_ct) {
+k_encrypt_s(RingDev rg, const uint2* __restrict__ pk, const int8_t* __restrict__ u, const int32_t* __restrict__ m,
+            const int8_t* __restrict__ e0, const int8_t* __restrict__ e1, uint32_t* __restrict__ ct_out, uint32_t n_ct) {
   using P = NttPlan<LOGN>;
   constexpr int N = 1 << LOGN;
   extern __shared__ uint32_t lds_u[];
@@ -391,7 +400,8 @@ k_encrypt_s(RingDev rg, const uint2* __restrict__ pk, const int8_t* __restrict__
   {  // inverse pass 0, + (m + e0) / + e1, store
     constexpr int R = P::R[0];
     using G = PassGeom<LOGN, 0, R>;
-    const int32_t* mc = me0 + c * N;
+    const int32_t* mc = m + c * N;
+    const int8_t* e0c = e0 + c * N;
     const int8_t* ec = e1 + c * N;
     uint32_t* out0 = ct_out + ((c * 2 + 0) * L + j) * N;
     uint32_t* out1 = ct_out + ((c * 2 + 1) * L + j) * N;
@@ -404,7 +414,7 @@ k_encrypt_s(RingDev rg, const uint2* __restrict__ pk, const int8_t* __restrict__
       for (int i = 0; i < G::E; ++i) {
         const int a = g + (i << G::LSTRIDE);
         // streaming output: keep it from evicting the key / twiddle tables that every workgroup shares
-        __builtin_nontemporal_store(add_mod(v[0][i], residue_of_signed(mc[a], q), q), out0 + a);
+        __builtin_nontemporal_store(add_mod(v[0][i], residue_of_signed(mc[a] + (int32_t)e0c[a], q), q), out0 + a);
         __builtin_nontemporal_store(add_mod(v[1][i], residue_of_signed((int32_t)ec[a], q), q), out1 + a);
       }
     }
@@ -933,7 +943,7 @@ he_status fail(he_status code, const std::string& msg) {
                   std::string(#expr) + ": " + hipGetErrorString(e_));                         \
   } while (0)
 
-constexpr uint64_t kCtChunk = 1024;  // ciphertexts per scratch chunk
+constexpr uint64_t kCtChunk = 2048;  // ciphertexts per scratch chunk (m+e0, u, e1: 192 MiB at N = 2^14)
 
 }  // namespace
 
@@ -1079,48 +1089,79 @@ void launch_ntt_batch(const RingDev& rg, bool inverse, int limb, uint32_t* polys
   }
 }
 
+// Scratch of one chunk of ciphertexts: plaintext m (int32) and the randomness u, e0, e1 (int8).
+struct EncScratch {
+  int32_t* m;
+  int8_t *u, *e0, *e1;
+};
+constexpr size_t kEncScratchBytesPerCoeff = 7;
+
+EncScratch carve_enc_scratch(void* ws, uint64_t chunk, size_t N) {
+  EncScratch s;
+  s.m = static_cast<int32_t*>(ws);
+  s.u = reinterpret_cast<int8_t*>(s.m + chunk * N);
+  s.e0 = s.u + chunk * N;
+  s.e1 = s.e0 + chunk * N;
+  return s;
+}
+
+// Encode n_ct ciphertexts' slots into m_out; when `rnd` is given, also draw their randomness
+// (specialised sizes do it inside the encoder kernel, the generic path with k_sample).
 he_status launch_encode(he_ctx* ctx, const MaskDev& mk, const float* w, const float* slots, uint64_t first_ct,
-                        uint64_t n_ct, int32_t* m_out, hipStream_t st) {
-  const uint32_t n = ctx->ring.N / 2;
+                        uint64_t n_ct, int32_t* m_out, const EncScratch* rnd, uint64_t seed, uint32_t client, hipStream_t st) {
+  const RingDev& rg = ctx->ring;
+  const uint32_t n = rg.N / 2;
+  const uint2 key = make_uint2((uint32_t)seed, (uint32_t)(seed >> 32));
+  int8_t* u = rnd ? rnd->u : nullptr;
+  int8_t* e0 = rnd ? rnd->e0 : nullptr;
+  int8_t* e1 = rnd ? rnd->e1 : nullptr;
+  bool sampled = false;
   {
     KernelTimer timer_(ctx, KID_ENCODE, st);
-    if (ctx->ring.logN == 14)
-      hipLaunchKernelGGL(k_encode_r<14>, dim3((uint32_t)n_ct), dim3(FftPlan<12>::NT), static_fft_lds_bytes(12), st, ctx->ring, mk, w,
-                         slots, first_ct, m_out);
-    else if (ctx->ring.logN == 13)
-      hipLaunchKernelGGL(k_encode_r<13>, dim3((uint32_t)n_ct), dim3(FftPlan<11>::NT), static_fft_lds_bytes(11), st, ctx->ring, mk, w,
-                         slots, first_ct, m_out);
-    else
-      hipLaunchKernelGGL(k_encode, dim3((uint32_t)n_ct), dim3(fft_threads(n)), fft_lds_bytes(n), st, ctx->ring, mk, w, slots,
-                         first_ct, m_out);
+    if (rg.logN == 14) {
+      hipLaunchKernelGGL(k_encode_r<14>, dim3((uint32_t)n_ct), dim3(FftPlan<12>::NT), static_fft_lds_bytes(12), st, rg, mk, w, slots,
+                         first_ct, m_out, key, client, u, e0, e1);
+      sampled = true;
+    } else if (rg.logN == 13) {
+      hipLaunchKernelGGL(k_encode_r<13>, dim3((uint32_t)n_ct), dim3(FftPlan<11>::NT), static_fft_lds_bytes(11), st, rg, mk, w, slots,
+                         first_ct, m_out, key, client, u, e0, e1);
+      sampled = true;
+    } else {
+      hipLaunchKernelGGL(k_encode, dim3((uint32_t)n_ct), dim3(fft_threads(n)), fft_lds_bytes(n), st, rg, mk, w, slots, first_ct, m_out);
+    }
   }
+  HIP_TRY(hipGetLastError());
+  if (rnd && !sampled) {
+    KernelTimer timer_(ctx, KID_SAMPLE, st);
+    hipLaunchKernelGGL(k_sample, dim3((uint32_t)n_ct), dim3(256), 0, st, rg, key, client, first_ct, rnd->u, rnd->e0, rnd->e1);
+    HIP_TRY(hipGetLastError());
+  }
+  return HE_OK;
+}
+
+he_status launch_sample(he_ctx* ctx, uint64_t seed, uint32_t client, uint64_t first_ct, uint64_t n_ct, const EncScratch& rnd,
+                        hipStream_t st) {
+  const uint2 key = make_uint2((uint32_t)seed, (uint32_t)(seed >> 32));
+  KernelTimer timer_(ctx, KID_SAMPLE, st);
+  hipLaunchKernelGGL(k_sample, dim3((uint32_t)n_ct), dim3(256), 0, st, ctx->ring, key, client, first_ct, rnd.u, rnd.e0, rnd.e1);
   HIP_TRY(hipGetLastError());
   return HE_OK;
 }
 
-he_status launch_sample_encrypt(he_ctx* ctx, const he_pk* pk, uint64_t seed, uint32_t client, uint64_t first_ct,
-                                uint64_t n_ct, const int32_t* m_in, int32_t* me0, int8_t* u, int8_t* e1,
-                                uint32_t* ct_out, hipStream_t st) {
+he_status launch_encrypt(he_ctx* ctx, const he_pk* pk, uint64_t n_ct, const int32_t* m, const EncScratch& rnd, uint32_t* ct_out,
+                         hipStream_t st) {
   const RingDev& rg = ctx->ring;
-  const uint2 key = make_uint2((uint32_t)seed, (uint32_t)(seed >> 32));
-  {
-    KernelTimer timer_(ctx, KID_SAMPLE, st);
-    hipLaunchKernelGGL(k_sample, dim3((uint32_t)n_ct), dim3(256), 0, st, rg, key, client, first_ct, m_in, me0, u, e1);
-  }
-  HIP_TRY(hipGetLastError());
-  {
-    KernelTimer timer_(ctx, KID_ENCRYPT, st);
-    const dim3 grid(rg.L, (uint32_t)n_ct);
-    const dim3 grid_x((uint32_t)((n_ct + 7) / 8) * 8 * rg.L);  // XCD-aware linear grid, see k_encrypt_s
-    if (rg.logN == 14)
-      hipLaunchKernelGGL(k_encrypt_s<14>, grid_x, dim3(NttPlan<14>::NT), static_lds_bytes(14, 2), st, rg, pk->tab, u, me0, e1, ct_out,
-                         (uint32_t)n_ct);
-    else if (rg.logN == 13)
-      hipLaunchKernelGGL(k_encrypt_s<13>, grid_x, dim3(NttPlan<13>::NT), static_lds_bytes(13, 2), st, rg, pk->tab, u, me0, e1, ct_out,
-                         (uint32_t)n_ct);
-    else
-      hipLaunchKernelGGL(k_encrypt, grid, dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 2), st, rg, pk->tab, u, me0, e1, ct_out);
-  }
+  KernelTimer timer_(ctx, KID_ENCRYPT, st);
+  const dim3 grid(rg.L, (uint32_t)n_ct);
+  const dim3 grid_x((uint32_t)((n_ct + 7) / 8) * 8 * rg.L);  // XCD-aware linear grid, see k_encrypt_s
+  if (rg.logN == 14)
+    hipLaunchKernelGGL(k_encrypt_s<14>, grid_x, dim3(NttPlan<14>::NT), static_lds_bytes(14, 2), st, rg, pk->tab, rnd.u, m, rnd.e0, rnd.e1,
+                       ct_out, (uint32_t)n_ct);
+  else if (rg.logN == 13)
+    hipLaunchKernelGGL(k_encrypt_s<13>, grid_x, dim3(NttPlan<13>::NT), static_lds_bytes(13, 2), st, rg, pk->tab, rnd.u, m, rnd.e0, rnd.e1,
+                       ct_out, (uint32_t)n_ct);
+  else
+    hipLaunchKernelGGL(k_encrypt, grid, dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 2), st, rg, pk->tab, rnd.u, m, rnd.e0, rnd.e1, ct_out);
   HIP_TRY(hipGetLastError());
   return HE_OK;
 }
@@ -1636,17 +1677,15 @@ he_status he_encrypt_masked(he_ctx* ctx, const he_pk* pk, const he_mask* mask, u
   const uint64_t chunk = std::min<uint64_t>(kCtChunk, n_ct);
   const size_t N = rg.N;
   if (chunk) {
-    s = ensure_ws(ctx, chunk * N * 6);  // int32 me0 + int8 u + int8 e1
+    s = ensure_ws(ctx, chunk * N * kEncScratchBytesPerCoeff);
     if (s != HE_OK) return s;
   }
-  int32_t* me0 = static_cast<int32_t*>(ctx->ws);
-  int8_t* u = reinterpret_cast<int8_t*>(me0 + chunk * N);
-  int8_t* e1 = u + chunk * N;
+  const EncScratch sc = carve_enc_scratch(ctx->ws, chunk, N);
   for (uint64_t c0 = 0; c0 < n_ct; c0 += chunk) {
     const uint64_t cn = std::min<uint64_t>(chunk, n_ct - c0);
-    s = launch_encode(ctx, mk, w_dev, nullptr, c0, cn, me0, st);
+    s = launch_encode(ctx, mk, w_dev, nullptr, c0, cn, sc.m, &sc, seed, client_id, st);
     if (s != HE_OK) return s;
-    s = launch_sample_encrypt(ctx, pk, seed, client_id, c0, cn, me0, me0, u, e1, ct_out_dev + c0 * 2 * rg.L * N, st);
+    s = launch_encrypt(ctx, pk, cn, sc.m, sc, ct_out_dev + c0 * 2 * rg.L * N, st);
     if (s != HE_OK) return s;
   }
   if (n_plain) {
@@ -1781,7 +1820,7 @@ he_status he_debug_encode(he_ctx* ctx, const float* slots_dev, uint64_t n_ct, in
   if (!slots_dev || !m_out_dev) return fail(HE_ERR_INVALID_ARG, "null argument");
   if (n_ct >= (1ull << 31)) return fail(HE_ERR_INVALID_ARG, "too many ciphertexts");
   MaskDev mk{};
-  return launch_encode(ctx, mk, nullptr, slots_dev, 0, n_ct, m_out_dev, static_cast<hipStream_t>(stream));
+  return launch_encode(ctx, mk, nullptr, slots_dev, 0, n_ct, m_out_dev, nullptr, 0, 0, static_cast<hipStream_t>(stream));
 }
 
 he_status he_debug_encrypt_plain(he_ctx* ctx, const he_pk* pk, uint64_t seed, uint32_t client_id, uint64_t first_ct,
@@ -1795,15 +1834,14 @@ he_status he_debug_encrypt_plain(he_ctx* ctx, const he_pk* pk, uint64_t seed, ui
   const RingDev& rg = ctx->ring;
   const size_t N = rg.N;
   const uint64_t chunk = std::min<uint64_t>(kCtChunk, n_ct);
-  s = ensure_ws(ctx, chunk * N * 6);
+  s = ensure_ws(ctx, chunk * N * kEncScratchBytesPerCoeff);
   if (s != HE_OK) return s;
-  int32_t* me0 = static_cast<int32_t*>(ctx->ws);
-  int8_t* u = reinterpret_cast<int8_t*>(me0 + chunk * N);
-  int8_t* e1 = u + chunk * N;
+  const EncScratch sc = carve_enc_scratch(ctx->ws, chunk, N);
   for (uint64_t c0 = 0; c0 < n_ct; c0 += chunk) {
     const uint64_t cn = std::min<uint64_t>(chunk, n_ct - c0);
-    s = launch_sample_encrypt(ctx, pk, seed, client_id, first_ct + c0, cn, m_dev + c0 * N, me0, u, e1,
-                              ct_out_dev + c0 * 2 * rg.L * N, st);
+    s = launch_sample(ctx, seed, client_id, first_ct + c0, cn, sc, st);
+    if (s != HE_OK) return s;
+    s = launch_encrypt(ctx, pk, cn, m_dev + c0 * N, sc, ct_out_dev + c0 * 2 * rg.L * N, st);
     if (s != HE_OK) return s;
   }
   return HE_OK;

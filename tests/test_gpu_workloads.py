@@ -33,7 +33,7 @@ def he():
 
 
 def _sample_cts(n_ct, extra=2, seed=0):
-    cand = {0, n_ct - 1, n_ct // 2, 1023, 1024, n_ct - 2}
+    cand = {0, n_ct - 1, n_ct // 2, 2047, 2048, n_ct - 2}          # 2048 = scratch chunk boundary inside the library
     rs = np.random.default_rng(seed)
     cand |= set(int(x) for x in rs.integers(0, n_ct, extra))
     return sorted(c for c in cand if 0 <= c < n_ct)
