@@ -23,14 +23,17 @@ HBM_PEAK_GBS = 8000.0
 # at one wave64 instruction per 4 cycles per SIMD on gfx950 (measured), so this is the peak
 # for the integer butterfly instruction mix.
 ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
-OPS_BUTTERFLY = 12   # Shoup product (mul_hi, 2 mul_lo, sub) + 2 (its reduction) + 3 (mod add) + 3 (mod sub)
-OPS_POINTWISE = 6    # Shoup product + reduction
+OPS_BUTTERFLY_FWD = 12   # Shoup product (mul_hi, 2 mul_lo, sub) + 2 (its reduction) + 3 (mod add) + 3 (mod sub)
+OPS_BUTTERFLY_INV = 11   # mod add (3) + x - y + q (2) + Shoup product (4) + its reduction (2)
+OPS_POINTWISE = 6        # Shoup product + reduction
 OPS_FINAL_ADD = 3
 
 
 def encrypt_ops_per_ct(N, L):
+    """One forward and two inverse transforms per limb, two key products and two final additions per coefficient."""
     log_n = N.bit_length() - 1
-    return L * (3 * (N // 2) * log_n * OPS_BUTTERFLY + 2 * N * OPS_POINTWISE + 2 * N * OPS_FINAL_ADD)
+    bfly = (N // 2) * log_n
+    return L * (bfly * (OPS_BUTTERFLY_FWD + 2 * OPS_BUTTERFLY_INV) + 2 * N * OPS_POINTWISE + 2 * N * OPS_FINAL_ADD)
 
 
 def measured_traffic(workload):
@@ -159,7 +162,8 @@ def main():
     he.he_debug_timing_enable(ctx, False)
     ntt_coeff_per_s = batch * N * ntt_launches / (ntt_ms * 1e-3)
     log_n = N.bit_length() - 1
-    ntt_tops = ntt_coeff_per_s * (log_n / 2) * OPS_BUTTERFLY / 1e12
+    # forward and inverse launches alternate: average butterfly cost, plus the inverse's 1/N product on every other launch
+    ntt_tops = ntt_coeff_per_s * ((log_n / 2) * (OPS_BUTTERFLY_FWD + OPS_BUTTERFLY_INV) / 2 + OPS_POINTWISE / 2) / 1e12
     roofline_ntt = {"kernel": "k_ntt_batch_s", "bound": "alu", "achieved": ntt_tops, "peak": ALU_PEAK_TOPS, "unit": "TOP/s",
                     "frac": ntt_tops / ALU_PEAK_TOPS, "traffic": measured_traffic(w.name).get("k_ntt_batch"),
                     "algorithmic_bytes_per_launch": batch * N * 8, "avg_launch_ms": ntt_ms / ntt_launches,
@@ -182,7 +186,7 @@ def main():
     agg_ms, agg_launches = kern["aggregate"]
     enc_ops = encrypt_ops_per_ct(N, L) * n_ct * K * args.steps           # all launches of the timed region
     enc_tops = enc_ops / (enc_ms * 1e-3) / 1e12 if enc_ms else 0.0
-    enc_bytes = (8 * L + 6) * N * n_ct * K * args.steps                  # 2*L*N residues written + m+e0, u, e1 read once
+    enc_bytes = (8 * L + 7) * N * n_ct * K * args.steps                  # 2*L*N residues written + m (int32), u, e0, e1 (int8) read once
     agg_bytes = n_ct * 2 * N * 4 * (K * L + (L - 1)) * args.steps
     agg_gbs = agg_bytes / (agg_ms * 1e-3) / 1e9 if agg_ms else 0.0
     dominant = max(kern, key=lambda k: kern[k][0])
