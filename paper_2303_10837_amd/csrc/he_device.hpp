@@ -39,13 +39,17 @@ __device__ __forceinline__ uint32_t mul_shoup(uint32_t y, uint2 w, uint32_t q) {
   return csub(mul_shoup_lazy(y, w, q), q);
 }
 
-// Signed small integer (|x| < 2^31) to its residue in [0, q), q in (2^30, 2^31).
+// Signed integer (any int32) to its residue in [0, q), q in (2^30, 2^31): a negative x gets
+// 2q added (2q > 2^31, so the sum is positive and below 2q; a non-negative x is below 2^31 < 2q
+// already), then one conditional subtraction.
 __device__ __forceinline__ uint32_t residue_of_signed(int32_t x, uint32_t q) {
-  int64_t r = x;
-  if (r < 0) r += q;
-  if (r < 0) r += q;
-  if (r >= (int64_t)q) r -= q;
-  return (uint32_t)r;
+  const uint32_t t = (uint32_t)x + ((uint32_t)(x >> 31) & (2u * q));
+  return csub(t, q);
+}
+
+// Same for |x| < q (sampled ternary / centred-binomial values): negative x gets q added.
+__device__ __forceinline__ uint32_t residue_of_small(int32_t x, uint32_t q) {
+  return (uint32_t)x + ((uint32_t)(x >> 31) & q);
 }
 
 // ---------------------------------------------------------------------------------------

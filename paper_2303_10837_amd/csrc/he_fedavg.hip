@@ -345,18 +345,22 @@ __device__ __forceinline__ void load_key8(const uint2* __restrict__ key, int bas
   }
 }
 
+// One LDS buffer per workgroup (two workgroups per CU) and at most 64 registers per thread (8
+// waves per SIMD): the kernel waits on table loads from L2 most of the time it is not computing,
+// and resident waves are what hides that.  The two inverse transforms (c0, c1) run one after the
+// other through the same buffer; after the fused middle pass the second polynomial waits in this
+// workgroup's own c1 output row (written and read back by the same thread, normally from L2).
 template <int LOGN>
-__global__ void __launch_bounds__(NttPlan<LOGN>::NT)
+__global__ void __launch_bounds__(NttPlan<LOGN>::NT, 8)
 k_encrypt_s(RingDev rg, const uint2* __restrict__ pk, const int8_t* __restrict__ u, const int32_t* __restrict__ m,
             const int8_t* __restrict__ e0, const int8_t* __restrict__ e1, uint32_t* __restrict__ ct_out, uint32_t n_ct) {
   using P = NttPlan<LOGN>;
-  constexpr int N = 1 << LOGN;
+  constexpr int N = 1 << LOGN, NT = P::NT;
   extern __shared__ uint32_t lds_u[];
   uint32_t* A = lds_u;
-  uint32_t* B = lds_u + spad(N);
   const uint32_t L = rg.L;
   // Workgroups are dealt to the 8 XCDs round-robin by linear id; the L limb-workgroups of one
-  // ciphertext read the same u / m+e0 / e1, so they are placed on the same XCD (one L2) at
+  // ciphertext read the same u / m / e0 / e1, so they are placed on the same XCD (one L2) at
   // consecutive slots: id = slot * 8 + xcd, slot = (c / 8) * L + limb, xcd = c % 8.
   const uint32_t slot = blockIdx.x >> 3;
   const uint32_t j = slot % L;
@@ -366,67 +370,81 @@ k_encrypt_s(RingDev rg, const uint2* __restrict__ pk, const int8_t* __restrict__
   const uint2* twf = rg.tw_fwd + (size_t)j * N;
   const uint2* twi = rg.tw_inv + (size_t)j * N;
   const int8_t* uc = u + c * N;
-  fwd_head<LOGN>(A, twf, q, [=](int a) {
-    const int v = uc[a];
-    return (uint32_t)(v < 0 ? v + (int)q : v);
-  });
-  {  // forward pass 3, product with b^ and a^, inverse pass 3: all on the same 8 coefficients
-    constexpr int S0 = P::S[3], R = P::R[3];
-    static_assert(R == 3, "the fused middle pass works on groups of 8");
-    using G = PassGeom<LOGN, S0, R>;
+  uint32_t* const out0 = ct_out + ((c * 2 + 0) * L + j) * N;
+  uint32_t* const out1 = ct_out + ((c * 2 + 1) * L + j) * N;
+  fwd_head<LOGN, NT>(A, twf, q, [=](int a) { return residue_of_small((int32_t)uc[a], q); });
+  constexpr int S3 = P::S[3], R3 = P::R[3];
+  static_assert(R3 == 3, "the fused middle pass works on groups of 8");
+  constexpr int IT3 = OwnedIters<LOGN, 3, NT>::value;
+  {  // forward pass 3, product with b^ / a^, inverse pass 3: all on the same 8 coefficients
     const uint2* kb = pk + ((size_t)0 * L + j) * N;
     const uint2* ka = pk + ((size_t)1 * L + j) * N;
-    for (int g = threadIdx.x; g < G::GROUPS; g += P::NT) {
-      uint32_t v[1][8];
-      lds_load_group<LOGN, S0, R>(A, g, v[0]);
-      bfly_stages<LOGN, S0, R, false, 1>(v, g, twf, q);
-      uint2 k0[8], k1[8];
-      load_key8(kb, g << 3, k0);
-      load_key8(ka, g << 3, k1);
-      uint32_t w[2][8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        w[0][i] = mul_shoup(v[0][i], k0[i], q);
-        w[1][i] = mul_shoup(v[0][i], k1[i], q);
-      }
-      bfly_stages<LOGN, S0, R, true, 2>(w, g, twi, q);
-      lds_store_group<LOGN, S0, R>(A, g, w[0]);
-      lds_store_group<LOGN, S0, R>(B, g, w[1]);
+    for (int it = 0; it < IT3; ++it) {
+      const int g = owned_group<LOGN, 3, NT>(it);
+      uint32_t v[1][8];
+      lds_load_group<LOGN, S3, R3>(A, g, v[0]);
+      bfly_stages<LOGN, S3, R3, false, 1, true>(v, g, twf, q);
+      uint2 k[8];
+      uint32_t w[1][8];
+      load_key8(kb, g << 3, k);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) w[0][i] = mul_shoup(v[0][i], k[i], q);
+      bfly_stages<LOGN, S3, R3, true, 1>(w, g, twi, q);
+      lds_store_group<LOGN, S3, R3>(A, g, w[0]);
+      load_key8(ka, g << 3, k);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) w[0][i] = mul_shoup(v[0][i], k[i], q);
+      bfly_stages<LOGN, S3, R3, true, 1>(w, g, twi, q);
+      uint4* park = reinterpret_cast<uint4*>(out1 + (g << 3));
+      park[0] = make_uint4(w[0][0], w[0][1], w[0][2], w[0][3]);
+      park[1] = make_uint4(w[0][4], w[0][5], w[0][6], w[0][7]);
     }
   }
-  __syncthreads();
-  uint32_t* const xs[2] = {A, B};
-  inv_middle<LOGN, 2>(xs, twi, q);
-  {  // inverse pass 0, + (m + e0) / + e1, store
-    constexpr int R = P::R[0];
-    using G = PassGeom<LOGN, 0, R>;
-    const int32_t* mc = m + c * N;
-    const int8_t* e0c = e0 + c * N;
-    const int8_t* ec = e1 + c * N;
-    uint32_t* out0 = ct_out + ((c * 2 + 0) * L + j) * N;
-    uint32_t* out1 = ct_out + ((c * 2 + 1) * L + j) * N;
-    for (int g = threadIdx.x; g < G::GROUPS; g += P::NT) {
-      uint32_t v[2][1 << R];
-      lds_load_group<LOGN, 0, R>(A, g, v[0]);
-      lds_load_group<LOGN, 0, R>(B, g, v[1]);
-      bfly_stages<LOGN, 0, R, true, 2>(v, 0, twi, q);
+  uint32_t* const xs[1] = {A};
+  constexpr int R0 = P::R[0];
+  using G0 = PassGeom<LOGN, 0, R0>;
+  const int32_t* mc = m + c * N;
+  const int8_t* e0c = e0 + c * N;
+  const int8_t* e1c = e1 + c * N;
 #pragma unroll
-      for (int i = 0; i < G::E; ++i) {
-        const int a = g + (i << G::LSTRIDE);
-        // streaming output: keep it from evicting the key / twiddle tables that every workgroup shares
-        __builtin_nontemporal_store(add_mod(v[0][i], residue_of_signed(mc[a] + (int32_t)e0c[a], q), q), out0 + a);
-        __builtin_nontemporal_store(add_mod(v[1][i], residue_of_signed((int32_t)ec[a], q), q), out1 + a);
+  for (int poly = 0; poly < 2; ++poly) {
+    if (poly == 1) {
+      __syncthreads();  // every wave's reads of the first polynomial are done
+#pragma unroll
+      for (int it = 0; it < IT3; ++it) {
+        const int g = owned_group<LOGN, 3, NT>(it);
+        const uint4* park = reinterpret_cast<const uint4*>(out1 + (g << 3));
+        const uint4 p0 = park[0], p1 = park[1];
+        const uint32_t back[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+        lds_store_group<LOGN, S3, R3>(A, g, back);
+      }
+    }
+    inv_middle<LOGN, 1, NT>(xs, twi, q);
+    uint32_t* out = poly == 0 ? out0 : out1;
+    // inverse pass 0, + (m + e0) or + e1, streaming store (kept from evicting the key / twiddle
+    // tables that every workgroup shares)
+#pragma unroll
+    for (int g = threadIdx.x; g < G0::GROUPS; g += NT) {
+      uint32_t v[1][1 << R0];
+      lds_load_group<LOGN, 0, R0>(A, g, v[0]);
+      bfly_stages<LOGN, 0, R0, true, 1>(v, 0, twi, q);
+#pragma unroll
+      for (int i = 0; i < G0::E; ++i) {
+        const int a = g + (i << G0::LSTRIDE);
+        const uint32_t r = poly == 0 ? residue_of_signed(mc[a] + (int32_t)e0c[a], q) : residue_of_small((int32_t)e1c[a], q);
+        __builtin_nontemporal_store(add_mod(v[0][i], r, q), out + a);
       }
     }
   }
 }
 
 template <int LOGN>
-__global__ void __launch_bounds__(NttPlan<LOGN>::NT)
+__global__ void __launch_bounds__(NttPlan<LOGN>::NT, 8)  // two workgroups per CU, 8 waves per SIMD
 k_decrypt_s(RingDev rg, const uint2* __restrict__ sk, const uint32_t* __restrict__ ct, uint32_t level,
             uint32_t* __restrict__ d_out) {
   using P = NttPlan<LOGN>;
-  constexpr int N = 1 << LOGN;
+  constexpr int N = 1 << LOGN, NT = P::NT;
   extern __shared__ uint32_t lds_u[];
   uint32_t* A = lds_u;
   const uint32_t j = blockIdx.x;
@@ -438,15 +456,16 @@ k_decrypt_s(RingDev rg, const uint2* __restrict__ sk, const uint32_t* __restrict
   const uint32_t* c1 = ct + ((c * 2 + 1) * level + j) * N;
   uint32_t* out = d_out + (c * level + j) * N;
   const uint2* key = sk + (size_t)j * N;
-  fwd_head<LOGN>(A, twf, q, [=](int a) { return c1[a]; });
+  fwd_head<LOGN, NT>(A, twf, q, [=](int a) { return c1[a]; });
   {
     constexpr int S0 = P::S[3], R = P::R[3];
     static_assert(R == 3, "the fused middle pass works on groups of 8");
-    using G = PassGeom<LOGN, S0, R>;
-    for (int g = threadIdx.x; g < G::GROUPS; g += P::NT) {
+#pragma unroll
+    for (int it = 0; it < OwnedIters<LOGN, 3, NT>::value; ++it) {
+      const int g = owned_group<LOGN, 3, NT>(it);
       uint32_t v[1][8];
       lds_load_group<LOGN, S0, R>(A, g, v[0]);
-      bfly_stages<LOGN, S0, R, false, 1>(v, g, twf, q);
+      bfly_stages<LOGN, S0, R, false, 1, true>(v, g, twf, q);
       uint2 k0[8];
       load_key8(key, g << 3, k0);
 #pragma unroll
@@ -455,13 +474,13 @@ k_decrypt_s(RingDev rg, const uint2* __restrict__ sk, const uint32_t* __restrict
       lds_store_group<LOGN, S0, R>(A, g, v[0]);
     }
   }
-  __syncthreads();
   uint32_t* const xs[1] = {A};
-  inv_middle<LOGN, 1>(xs, twi, q);
+  inv_middle<LOGN, 1, NT>(xs, twi, q);
   {
     constexpr int R = P::R[0];
     using G = PassGeom<LOGN, 0, R>;
-    for (int g = threadIdx.x; g < G::GROUPS; g += P::NT) {
+#pragma unroll
+    for (int g = threadIdx.x; g < G::GROUPS; g += NT) {
       uint32_t v[1][1 << R];
       lds_load_group<LOGN, 0, R>(A, g, v[0]);
       bfly_stages<LOGN, 0, R, true, 1>(v, 0, twi, q);
@@ -489,7 +508,9 @@ k_ntt_batch_s(RingDev rg, int limb, uint32_t* __restrict__ polys) {
   if (!INV) {
     const uint2* twf = rg.tw_fwd + (size_t)j * N;
     fwd_head<LOGN>(A, twf, q, [=](int a) { return x[a]; });
-    for (int g = threadIdx.x; g < G3::GROUPS; g += P::NT) {
+#pragma unroll
+    for (int it = 0; it < OwnedIters<LOGN, 3, P::NT>::value; ++it) {
+      const int g = owned_group<LOGN, 3, P::NT>(it);
       uint32_t v[1][1 << R3];
       lds_load_group<LOGN, S3, R3>(A, g, v[0]);
       bfly_stages<LOGN, S3, R3, false, 1>(v, g, twf, q);
@@ -500,7 +521,9 @@ k_ntt_batch_s(RingDev rg, int limb, uint32_t* __restrict__ polys) {
   } else {
     const uint2* twi = rg.tw_inv + (size_t)j * N;
     const uint2 ninv = rg.ninv[j];
-    for (int g = threadIdx.x; g < G3::GROUPS; g += P::NT) {
+#pragma unroll
+    for (int it = 0; it < OwnedIters<LOGN, 3, P::NT>::value; ++it) {
+      const int g = owned_group<LOGN, 3, P::NT>(it);
       uint32_t v[1][1 << R3];
       const uint4* in = reinterpret_cast<const uint4*>(x + (g << R3));
 #pragma unroll
@@ -511,7 +534,6 @@ k_ntt_batch_s(RingDev rg, int limb, uint32_t* __restrict__ polys) {
       bfly_stages<LOGN, S3, R3, true, 1>(v, g, twi, q);
       lds_store_group<LOGN, S3, R3>(A, g, v[0]);
     }
-    __syncthreads();
     uint32_t* const xs[1] = {A};
     inv_middle<LOGN, 1>(xs, twi, q);
     constexpr int R0 = P::R[0];
@@ -1155,10 +1177,10 @@ he_status launch_encrypt(he_ctx* ctx, const he_pk* pk, uint64_t n_ct, const int3
   const dim3 grid(rg.L, (uint32_t)n_ct);
   const dim3 grid_x((uint32_t)((n_ct + 7) / 8) * 8 * rg.L);  // XCD-aware linear grid, see k_encrypt_s
   if (rg.logN == 14)
-    hipLaunchKernelGGL(k_encrypt_s<14>, grid_x, dim3(NttPlan<14>::NT), static_lds_bytes(14, 2), st, rg, pk->tab, rnd.u, m, rnd.e0, rnd.e1,
+    hipLaunchKernelGGL(k_encrypt_s<14>, grid_x, dim3(NttPlan<14>::NT), static_lds_bytes(14, 1), st, rg, pk->tab, rnd.u, m, rnd.e0, rnd.e1,
                        ct_out, (uint32_t)n_ct);
   else if (rg.logN == 13)
-    hipLaunchKernelGGL(k_encrypt_s<13>, grid_x, dim3(NttPlan<13>::NT), static_lds_bytes(13, 2), st, rg, pk->tab, rnd.u, m, rnd.e0, rnd.e1,
+    hipLaunchKernelGGL(k_encrypt_s<13>, grid_x, dim3(NttPlan<13>::NT), static_lds_bytes(13, 1), st, rg, pk->tab, rnd.u, m, rnd.e0, rnd.e1,
                        ct_out, (uint32_t)n_ct);
   else
     hipLaunchKernelGGL(k_encrypt, grid, dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 2), st, rg, pk->tab, rnd.u, m, rnd.e0, rnd.e1, ct_out);
@@ -1428,11 +1450,11 @@ he_status he_ctx_create(const he_params* params, int device, he_ctx** out) {
   if (s == HE_OK) s = allow_lds(k_decrypt, ntt_lds_bytes(N, 1));
   if (s == HE_OK) s = allow_lds(k_ntt_batch<false>, ntt_lds_bytes(N, 1));
   if (s == HE_OK) s = allow_lds(k_ntt_batch<true>, ntt_lds_bytes(N, 1));
-  if (s == HE_OK && logN == 14) s = allow_lds(k_encrypt_s<14>, static_lds_bytes(14, 2));
+  if (s == HE_OK && logN == 14) s = allow_lds(k_encrypt_s<14>, static_lds_bytes(14, 1));
   if (s == HE_OK && logN == 14) s = allow_lds(k_decrypt_s<14>, static_lds_bytes(14, 1));
   if (s == HE_OK && logN == 14) s = allow_lds(k_ntt_batch_s<14, false>, static_lds_bytes(14, 1));
   if (s == HE_OK && logN == 14) s = allow_lds(k_ntt_batch_s<14, true>, static_lds_bytes(14, 1));
-  if (s == HE_OK && logN == 13) s = allow_lds(k_encrypt_s<13>, static_lds_bytes(13, 2));
+  if (s == HE_OK && logN == 13) s = allow_lds(k_encrypt_s<13>, static_lds_bytes(13, 1));
   if (s == HE_OK && logN == 13) s = allow_lds(k_decrypt_s<13>, static_lds_bytes(13, 1));
   if (s == HE_OK && logN == 13) s = allow_lds(k_ntt_batch_s<13, false>, static_lds_bytes(13, 1));
   if (s == HE_OK && logN == 13) s = allow_lds(k_ntt_batch_s<13, true>, static_lds_bytes(13, 1));

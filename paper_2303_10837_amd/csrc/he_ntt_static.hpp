@@ -50,7 +50,13 @@ struct PassGeom {
 };
 
 // R butterfly stages on NP register-resident groups that share their twiddles.
-template <int LOGN, int S0, int R, bool INV, int NP>
+//
+// Forward stages leave an output in [0, 2q) instead of [0, q) when its only next use is as the
+// multiplicand of a Shoup product (which accepts any 32-bit value): inside a pass that is
+// every element whose index has the next stage's pairing bit set (both outputs of a butterfly
+// share that bit); after the last stage of a pass only when the caller says so (LAZY_LAST: the
+// pass is followed by a pointwise key product).  Such a butterfly costs 9 operations, not 12.
+template <int LOGN, int S0, int R, bool INV, int NP, bool LAZY_LAST = false>
 __device__ __forceinline__ void bfly_stages(uint32_t (&v)[NP][1 << R], int b, const uint2* __restrict__ tw, uint32_t q) {
   using G = PassGeom<LOGN, S0, R>;
   constexpr int E = 1 << R;
@@ -64,12 +70,18 @@ __device__ __forceinline__ void bfly_stages(uint32_t (&v)[NP][1 << R], int b, co
       for (int i = 0; i < E; ++i) {
         if (i & half) continue;
         const uint2 w = twk[i >> (R - k)];
+        const bool lazy = (k + 1 < R) ? ((i & (half >> 1)) != 0) : LAZY_LAST;
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
           const uint32_t t = mul_shoup(v[p][i + half], w, q);
           const uint32_t x = v[p][i];
-          v[p][i] = add_mod(x, t, q);
-          v[p][i + half] = sub_mod(x, t, q);
+          if (lazy) {
+            v[p][i] = x + t;             // [0, 2q)
+            v[p][i + half] = x - t + q;  // (0, 2q)
+          } else {
+            v[p][i] = add_mod(x, t, q);
+            v[p][i + half] = sub_mod(x, t, q);
+          }
         }
       }
     }
@@ -122,13 +134,47 @@ __device__ __forceinline__ void lds_store_group(uint32_t* x, int g, const uint32
   }
 }
 
-// One LDS -> LDS pass over NP buffers that share twiddles.  No barrier inside.
-template <int LOGN, int PASS, bool INV, int NP>
+// Passes 1..3 never leave a block of N/16 consecutive coefficients (pass 1 starts at stage 4),
+// and one such block is exactly 64 pass-1 groups: one wavefront.  Wave w of a workgroup of NT
+// threads therefore OWNS blocks w, w + NT/64, ... through passes 1, 2 and 3 of the forward
+// transform and 3, 2, 1 of the inverse: the data it reads in one of these passes was written by
+// itself in the previous one, so those passes are separated by a wavefront-level ordering point
+// only, and a workgroup barrier is needed just around pass 0 (stride N/16, the whole polynomial).
+// owned_group(it) is the group index of this thread's it-th group of pass PASS.
+template <int LOGN, int PASS, int NT>
+__device__ __forceinline__ int owned_group(int it) {
+  using P = NttPlan<LOGN>;
+  static_assert(P::S[1] == 4 && PASS >= 1, "blocks of N/16 coefficients start at pass 1");
+  constexpr int GPB = ((1 << LOGN) / 16) >> P::R[PASS];  // groups per block in this pass
+  constexpr int NW = NT / 64;
+  static_assert(NT % 64 == 0 && 16 % NW == 0 && GPB % 64 == 0, "whole wavefronts per block");
+  const int local = it * 64 + (int)(threadIdx.x & 63);
+  return ((int)(threadIdx.x >> 6) + NW * (local / GPB)) * GPB + (local % GPB);
+}
+template <int LOGN, int PASS, int NT>
+struct OwnedIters {
+  static constexpr int value = (1 << (LOGN - NttPlan<LOGN>::R[PASS])) / NT;
+  static_assert((1 << (LOGN - NttPlan<LOGN>::R[PASS])) % NT == 0, "whole iterations");
+};
+
+// Ordering point between two passes that stay inside wave-owned blocks: this wavefront's LDS
+// writes are ordered before its later LDS reads.  No other wave is involved, so no s_barrier; the
+// fence is restricted to LDS so that global loads and stores stay in flight across it.
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup", "local");
+  __builtin_amdgcn_wave_barrier();
+}
+
+// One LDS -> LDS pass (1, 2 or 3) over NP buffers that share twiddles, on the groups this
+// wavefront owns.  No barrier inside.
+template <int LOGN, int PASS, bool INV, int NP, int NT = NttPlan<LOGN>::NT>
 __device__ __forceinline__ void lds_pass(uint32_t* const (&x)[NP], const uint2* __restrict__ tw, uint32_t q) {
   using P = NttPlan<LOGN>;
   constexpr int S0 = P::S[PASS], R = P::R[PASS];
   using G = PassGeom<LOGN, S0, R>;
-  for (int g = threadIdx.x; g < G::GROUPS; g += P::NT) {
+#pragma unroll
+  for (int it = 0; it < OwnedIters<LOGN, PASS, NT>::value; ++it) {
+    const int g = owned_group<LOGN, PASS, NT>(it);
     uint32_t v[NP][1 << R];
 #pragma unroll
     for (int p = 0; p < NP; ++p) lds_load_group<LOGN, S0, R>(x[p], g, v[p]);
@@ -139,15 +185,16 @@ __device__ __forceinline__ void lds_pass(uint32_t* const (&x)[NP], const uint2* 
 }
 
 // Forward transform of one polynomial: first pass reads through ld0(index), passes 0..2 end
-// in LDS buffer x (each followed by a barrier).  The LAST pass is left to the caller (it is
-// fused with whatever follows); use fwd_last_group() for it.
-template <int LOGN, class Load0>
+// in LDS buffer x.  The LAST pass is left to the caller (it is fused with whatever follows);
+// it must run on the caller's owned groups of pass 3, after which no barrier is needed either.
+template <int LOGN, int NT = NttPlan<LOGN>::NT, class Load0>
 __device__ __forceinline__ void fwd_head(uint32_t* x, const uint2* __restrict__ tw, uint32_t q, Load0 ld0) {
   using P = NttPlan<LOGN>;
   {
     constexpr int R = P::R[0];
     using G = PassGeom<LOGN, 0, R>;
-    for (int g = threadIdx.x; g < G::GROUPS; g += P::NT) {
+#pragma unroll
+    for (int g = threadIdx.x; g < G::GROUPS; g += NT) {
       uint32_t v[1][1 << R];
 #pragma unroll
       for (int i = 0; i < G::E; ++i) v[0][i] = ld0(g + (i << G::LSTRIDE));
@@ -157,19 +204,21 @@ __device__ __forceinline__ void fwd_head(uint32_t* x, const uint2* __restrict__ 
   }
   __syncthreads();
   uint32_t* const xs[1] = {x};
-  lds_pass<LOGN, 1, false, 1>(xs, tw, q);
-  __syncthreads();
-  lds_pass<LOGN, 2, false, 1>(xs, tw, q);
-  __syncthreads();
+  lds_pass<LOGN, 1, false, 1, NT>(xs, tw, q);
+  wave_lds_sync();
+  lds_pass<LOGN, 2, false, 1, NT>(xs, tw, q);
+  wave_lds_sync();
 }
 
-// Inverse passes 2 and 1 over NP buffers (each followed by a barrier); the caller does the
-// inverse of pass 3 before (fused) and of pass 0 after (fused with the store).
-template <int LOGN, int NP>
+// Inverse passes 2 and 1 over NP buffers, on owned groups; the caller does the inverse of pass
+// 3 before (fused, on its owned groups, no barrier in between) and of pass 0 after (fused with
+// the store).  Ends with the workgroup barrier that pass 0 needs.
+template <int LOGN, int NP, int NT = NttPlan<LOGN>::NT>
 __device__ __forceinline__ void inv_middle(uint32_t* const (&x)[NP], const uint2* __restrict__ tw, uint32_t q) {
-  lds_pass<LOGN, 2, true, NP>(x, tw, q);
-  __syncthreads();
-  lds_pass<LOGN, 1, true, NP>(x, tw, q);
+  wave_lds_sync();
+  lds_pass<LOGN, 2, true, NP, NT>(x, tw, q);
+  wave_lds_sync();
+  lds_pass<LOGN, 1, true, NP, NT>(x, tw, q);
   __syncthreads();
 }
 
