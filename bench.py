@@ -23,17 +23,33 @@ HBM_PEAK_GBS = 8000.0
 # at one wave64 instruction per 4 cycles per SIMD on gfx950 (measured), so this is the peak
 # for the integer butterfly instruction mix.
 ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
-OPS_BUTTERFLY_FWD = 12   # Shoup product (mul_hi, 2 mul_lo, sub) + 2 (its reduction) + 3 (mod add) + 3 (mod sub)
-OPS_BUTTERFLY_INV = 11   # mod add (3) + x - y + q (2) + Shoup product (4) + its reduction (2)
+# Operation counts of the integer butterflies as the kernels execute them (one 32-bit instruction each):
+OPS_BFLY_FWD = 12        # Shoup product (mul_hi, 2 mul_lo, sub) + its reduction (2) + modular add (3) + modular sub (3)
+OPS_BFLY_FWD_LAZY = 9    # outputs whose next use is a Shoup multiplicand stay in [0, 2q): add (1) + sub (2)
+OPS_BFLY_INV = 11        # modular add (3) + x - y + q (2) + Shoup product (4) + its reduction (2)
 OPS_POINTWISE = 6        # Shoup product + reduction
-OPS_FINAL_ADD = 3
+PASS_PLAN = {14: (4, 4, 3, 3), 13: (4, 3, 3, 3)}   # stages per LDS pass of the specialised transforms
+
+
+def fwd_ops_per_coeff(log_n, lazy_last):
+    """Forward transform: inside a pass half the butterflies of every stage but the last are lazy; the last stage of
+    the last pass is lazy when a key product follows (encrypt, decrypt).  Half a butterfly per coefficient and stage."""
+    plan = PASS_PLAN.get(log_n)
+    if plan is None:
+        return 0.5 * log_n * OPS_BFLY_FWD            # generic kernels: no lazy butterflies
+    ops = 0.0
+    for p, r in enumerate(plan):
+        ops += (r - 1) * 0.5 * (OPS_BFLY_FWD + OPS_BFLY_FWD_LAZY) / 2
+        ops += 0.5 * (OPS_BFLY_FWD_LAZY if (lazy_last and p == len(plan) - 1) else OPS_BFLY_FWD)
+    return ops
 
 
 def encrypt_ops_per_ct(N, L):
-    """One forward and two inverse transforms per limb, two key products and two final additions per coefficient."""
+    """Per limb: one forward and two inverse transforms, two key products, and per coefficient the residues of u (3),
+    m + e0 (1 + 5) and e1 (3) and two modular additions (3 each)."""
     log_n = N.bit_length() - 1
-    bfly = (N // 2) * log_n
-    return L * (bfly * (OPS_BUTTERFLY_FWD + 2 * OPS_BUTTERFLY_INV) + 2 * N * OPS_POINTWISE + 2 * N * OPS_FINAL_ADD)
+    per_coeff = fwd_ops_per_coeff(log_n, True) + 2 * 0.5 * log_n * OPS_BFLY_INV + 2 * OPS_POINTWISE + 3 + 6 + 3 + 6
+    return L * N * per_coeff
 
 
 def measured_traffic(workload):
@@ -78,6 +94,36 @@ def cpu_baseline(w, ws_host, alpha, runs, budget_s=15.0):
                       f"host has {os.cpu_count()} cores"}
 
 
+def aggregate_k_sweep(he, ctx, torch, n_ct=512, ks=(3, 8, 16, 32, 64, 128, 200), reps=5):
+    """Server-side cost against the number of clients (the paper's figure on up to 200 clients): he_aggregate alone on
+    K distinct ciphertext buffers of n_ct ciphertexts each, filled with uniform residues (timing does not depend on
+    the values; parity for large K is a test).  Above 64 clients the library folds 64 clients per launch into an
+    internal accumulator, whose extra traffic is part of the measured time but not of the algorithmic bytes."""
+    N, L = ctx.N, ctx.L
+    q_min = ctx.primes[-1]
+    bufs = [torch.randint(0, q_min, (n_ct, 2, L, N), dtype=torch.int32, device="cuda") for _ in range(max(ks))]
+    out = torch.empty((n_ct, 2, L - 1, N), dtype=torch.int32, device="cuda")
+    rows = []
+    for K in ks:
+        counts = np.random.default_rng(K).integers(100, 1001, K).astype(np.float64)
+        alpha = counts / counts.sum()
+        he.he_aggregate(ctx, alpha, bufs[:K], [None] * K, out, None)
+        torch.cuda.synchronize()
+        he.he_debug_timing_enable(ctx, True)
+        he.he_debug_timing_read(ctx)
+        for _ in range(reps):
+            he.he_aggregate(ctx, alpha, bufs[:K], [None] * K, out, None)
+        ms, launches = he.he_debug_timing_read(ctx)["aggregate"]
+        he.he_debug_timing_enable(ctx, False)
+        ms_call = ms / reps
+        alg = n_ct * 8 * N * (K * L + L - 1)
+        rows.append({"clients": K, "ms": ms_call, "launches_per_call": launches // reps,
+                     "encrypted_params_per_s": n_ct * (N // 2) / (ms_call * 1e-3),
+                     "algorithmic_GBps": alg / (ms_call * 1e-3) / 1e9, "frac_of_hbm_peak": alg / (ms_call * 1e-3) / 1e9 / HBM_PEAK_GBS})
+    del bufs
+    return {"n_ct": n_ct, "ring_degree": N, "limbs": L, "rows": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -85,6 +131,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="resnet18_full")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--k-sweep", action="store_true",
+                    help="also time he_aggregate alone for K = 3 ... 200 clients (server cost against the number of clients)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (known HBM traffic, for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -162,12 +210,13 @@ def main():
     he.he_debug_timing_enable(ctx, False)
     ntt_coeff_per_s = batch * N * ntt_launches / (ntt_ms * 1e-3)
     log_n = N.bit_length() - 1
-    # forward and inverse launches alternate: average butterfly cost, plus the inverse's 1/N product on every other launch
-    ntt_tops = ntt_coeff_per_s * ((log_n / 2) * (OPS_BUTTERFLY_FWD + OPS_BUTTERFLY_INV) / 2 + OPS_POINTWISE / 2) / 1e12
+    # forward and inverse launches alternate: average of the two, the inverse includes its 1/N product
+    ntt_ops_per_coeff = (fwd_ops_per_coeff(log_n, False) + 0.5 * log_n * OPS_BFLY_INV + OPS_POINTWISE) / 2
+    ntt_tops = ntt_coeff_per_s * ntt_ops_per_coeff / 1e12
     roofline_ntt = {"kernel": "k_ntt_batch_s", "bound": "alu", "achieved": ntt_tops, "peak": ALU_PEAK_TOPS, "unit": "TOP/s",
                     "frac": ntt_tops / ALU_PEAK_TOPS, "traffic": measured_traffic(w.name).get("k_ntt_batch"),
                     "algorithmic_bytes_per_launch": batch * N * 8, "avg_launch_ms": ntt_ms / ntt_launches,
-                    "launches": int(ntt_launches), "coeff_per_s": ntt_coeff_per_s,
+                    "launches": int(ntt_launches), "coeff_per_s": ntt_coeff_per_s, "ops_per_coeff": ntt_ops_per_coeff,
                     "hbm_GBps": ntt_coeff_per_s * 8 / 1e9, "hbm_frac": ntt_coeff_per_s * 8 / 1e9 / HBM_PEAK_GBS}
     del polys
     if args.calibrate_copy:
@@ -176,6 +225,8 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    k_sweep = aggregate_k_sweep(he, ctx, torch) if args.k_sweep else None
 
     # sanity: the decoded aggregate is FedAvg up to the CKKS noise (not part of the timing)
     ref = sum(float(a) * x.double() for a, x in zip(alpha, ws))
@@ -219,6 +270,8 @@ def main():
         "roofline": roofline, "roofline_aggregate": roofline_agg, "roofline_ntt": roofline_ntt,
         "max_abs_err_vs_float64_fedavg": max_err,
     }
+    if k_sweep is not None:
+        res["aggregate_k_sweep"] = k_sweep
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, ws_host, alpha, runs)
     print(json.dumps(res))

@@ -52,7 +52,7 @@ struct CrtArgs {
   uint32_t hw[kMaxLimbs];  // words of (Q' - 1) / 2
 };
 
-constexpr int kAggClients = 32;  // clients folded per aggregation launch
+constexpr int kAggClients = 64;  // clients folded per aggregation launch (their pointers and weights travel as kernel arguments: 2.5 KiB)
 
 struct AggArgs {
   const uint32_t* ct[kAggClients];

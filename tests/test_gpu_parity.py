@@ -112,7 +112,7 @@ def test_encrypt_given_plaintext(he, log2_n, limbs, eta):
         assert np.array_equal(ct[c], ref), (c,)
 
 
-@pytest.mark.parametrize("log2_n,limbs,K", [(4, 3, 3), (10, 2, 5), (13, 3, 3), (14, 4, 8), (10, 3, 1), (10, 3, 37), (10, 4, 70)])
+@pytest.mark.parametrize("log2_n,limbs,K", [(4, 3, 3), (10, 2, 5), (13, 3, 3), (14, 4, 8), (10, 3, 1), (10, 3, 37), (10, 4, 70), (10, 3, 200)])
 def test_aggregate_and_streaming(he, log2_n, limbs, K):
     ctx, _, p, _ = _setup(he, log2_n, limbs)
     rs = np.random.default_rng(3)
