@@ -64,17 +64,20 @@ def measured_traffic(workload):
     return out
 
 
-def cpu_baseline(w, ws_host, alpha, runs, budget_s=15.0):
+def cpu_baseline(w, ws_host, alpha, runs, budget_s=15.0, client_weighted=False):
     """Times the CPU oracle on a bounded sample of ciphertext indices of the same workload."""
     from oracle import fedavg as ofed, scheme as osch
     from oracle.params import Params
-    p = Params(w.log2_n, w.n_limbs, w.scale_bits, w.cbd_eta)
+    p = Params(w.log2_n, w.n_limbs - 1 if client_weighted else w.n_limbs, w.scale_bits, w.cbd_eta)
     keys = osch.keygen(p, w.seed)
     P = w.n_params
     enc_idx, _ = ofed.mask_indices(P, runs)
     n_ct = ofed.n_ciphertexts(p, len(enc_idx))
 
     def one(c):
+        if client_weighted:
+            cts = [ofed.encrypt_ct_weighted(p, keys, x, enc_idx, alpha[i], w.seed, i, c)[1] for i, x in enumerate(ws_host)]
+            return ofed.decode_ct_level(p, keys, osch.sum_ciphertexts(p, cts), p.n_limbs)
         cts = [ofed.encrypt_ct(p, keys, x, enc_idx, w.seed, i, c)[1] for i, x in enumerate(ws_host)]
         return ofed.decode_ct(p, keys, osch.aggregate(p, cts, alpha))
 
@@ -131,6 +134,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="resnet18_full")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--variant", default="server_weighted", choices=["server_weighted", "client_weighted"],
+                    help="client_weighted: clients encode alpha_i * W_i, the server only adds ciphertexts (no rescale), one limb fewer")
     ap.add_argument("--k-sweep", action="store_true",
                     help="also time he_aggregate alone for K = 3 ... 200 clients (server cost against the number of clients)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -147,7 +152,9 @@ def main():
     torch.cuda.set_device(0)
     w = si.WORKLOADS[args.workload]
     K = w.n_clients
-    ctx = he.Context(w.log2_n, w.n_limbs, w.scale_bits, w.cbd_eta)
+    client_weighted = args.variant == "client_weighted"
+    n_limbs = w.n_limbs - 1 if client_weighted else w.n_limbs     # no rescale: the level never drops
+    ctx = he.Context(w.log2_n, n_limbs, w.scale_bits, w.cbd_eta)
     keys = he.he_keygen(ctx, w.seed)
     starts, lens = si.mask_runs(w)
     runs = [(int(s), int(l)) for s, l in zip(starts, lens)]
@@ -158,7 +165,8 @@ def main():
     N, L, n_ct, P_enc = ctx.N, ctx.L, mask.n_ct, mask.P_enc
     cts = [torch.empty((n_ct, 2, L, N), dtype=torch.int32, device="cuda") for _ in range(K)]
     plains = [torch.empty((mask.n_plain,), dtype=torch.float32, device="cuda") for _ in range(K)]
-    ct_g = torch.empty((n_ct, 2, L - 1, N), dtype=torch.int32, device="cuda")
+    L_out = L if client_weighted else L - 1
+    ct_g = torch.empty((n_ct, 2, L_out, N), dtype=torch.int32, device="cuda")
     pl_g = torch.empty((mask.n_plain,), dtype=torch.float32, device="cuda")
     out = torch.empty((w.n_params,), dtype=torch.float32, device="cuda")
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
@@ -168,13 +176,22 @@ def main():
         if record:
             ev[0].record()
         for i in range(K):
-            he.he_encrypt_masked(ctx, keys, mask, w.seed, i, ws[i], cts[i], plains[i])
+            if client_weighted:
+                he.he_encrypt_masked_weighted(ctx, keys, mask, w.seed, i, alpha[i], ws[i], cts[i], plains[i])
+            else:
+                he.he_encrypt_masked(ctx, keys, mask, w.seed, i, ws[i], cts[i], plains[i])
         if record:
             ev[1].record()
-        he.he_aggregate(ctx, alpha, cts, plains, ct_g, pl_g)
+        if client_weighted:
+            he.he_aggregate_sum(ctx, cts, plains, ct_g, pl_g)
+        else:
+            he.he_aggregate(ctx, alpha, cts, plains, ct_g, pl_g)
         if record:
             ev[2].record()
-        he.he_decrypt_merge(ctx, keys, mask, ct_g, pl_g, out)
+        if client_weighted:
+            he.he_decrypt_merge_level(ctx, keys, mask, L, ct_g, pl_g, out)
+        else:
+            he.he_decrypt_merge(ctx, keys, mask, ct_g, pl_g, out)
         if record:
             ev[3].record()
 
@@ -238,7 +255,7 @@ def main():
     enc_ops = encrypt_ops_per_ct(N, L) * n_ct * K * args.steps           # all launches of the timed region
     enc_tops = enc_ops / (enc_ms * 1e-3) / 1e12 if enc_ms else 0.0
     enc_bytes = (8 * L + 7) * N * n_ct * K * args.steps                  # 2*L*N residues written + m (int32), u, e0, e1 (int8) read once
-    agg_bytes = n_ct * 2 * N * 4 * (K * L + (L - 1)) * args.steps
+    agg_bytes = n_ct * 2 * N * 4 * (K * L + L_out) * args.steps
     agg_gbs = agg_bytes / (agg_ms * 1e-3) / 1e9 if agg_ms else 0.0
     dominant = max(kern, key=lambda k: kern[k][0])
     traffic = measured_traffic(w.name)
@@ -258,7 +275,7 @@ def main():
         "value": K * P_enc / (ms_step * 1e-3), "unit": "params/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "u32", "data": "synthetic",
-        "config": {"workload": w.name, "clients": K, "params_per_client": w.n_params, "encrypted_params": P_enc,
+        "config": {"workload": w.name, "variant": args.variant, "clients": K, "params_per_client": w.n_params, "encrypted_params": P_enc,
                    "n_ct_per_client": n_ct, "ring_degree": N, "limbs": L, "scale_bits": w.scale_bits,
                    "value_definition": "clients * encrypted_params / step time; step = all clients encrypt + aggregate + decrypt"},
         "phases": {"encrypt_ms": phase_ms[0], "aggregate_ms": phase_ms[1], "decrypt_ms": phase_ms[2],
@@ -273,7 +290,7 @@ def main():
     if k_sweep is not None:
         res["aggregate_k_sweep"] = k_sweep
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(w, ws_host, alpha, runs)
+        res["cpu_baseline"] = cpu_baseline(w, ws_host, alpha, runs, client_weighted=client_weighted)
     print(json.dumps(res))
 
 

@@ -160,6 +160,31 @@ he_status he_decrypt_merge(he_ctx* ctx, const he_sk* sk, const he_mask* mask,
                            const uint32_t* ct_glob_dev, const float* plain_glob_dev,
                            float* w_out_dev, void* stream);
 
+/* ---- variant: weighing on the client ("scales each learner's local model parameters locally
+   rather than weighing ciphertexts on the server", Section "Comparison with Other FL Frameworks").
+   The client encodes alpha_i * W_i, the server only adds ciphertexts: no ciphertext-scalar
+   product, no rescale, and the level never drops, so a context with one limb fewer serves the
+   same plaintext range.  The paper notes the price: every client learns its own weight.
+   (A second price shows in the noise: K fresh encryption noises add up unweighted, so the slot
+   error grows like sqrt(K) instead of sqrt(sum alpha_i^2).) ------------------------------- */
+
+/* As he_encrypt_masked, but slot j carries alpha * w (product in float64, before encoding) and
+   the plaintext remainder holds float32(alpha * w).  0 < alpha <= 1. */
+he_status he_encrypt_masked_weighted(he_ctx* ctx, const he_pk* pk, const he_mask* mask,
+                                     uint64_t seed, uint32_t client_id, double alpha,
+                                     const float* w_dev, uint32_t* ct_out_dev,
+                                     float* plain_out_dev, void* stream);
+/* ct_out = sum_i ct_i (mod q_j) in all L limbs: uint32[n_ct][2][L][N], level L.  plain_out =
+   float32 of the float64 sum of the K remainders in client order.  Pointer arrays as in
+   he_aggregate.  Needs only the public context. */
+he_status he_aggregate_sum(he_ctx* ctx, uint32_t K, const uint32_t* const* ct_in_dev,
+                           const float* const* plain_in_dev, uint64_t n_ct, uint64_t n_plain,
+                           uint32_t* ct_out_dev, float* plain_out_dev, void* stream);
+/* he_decrypt_merge for a global ciphertext at any level 1..L: uint32[n_ct][2][level][N]. */
+he_status he_decrypt_merge_level(he_ctx* ctx, const he_sk* sk, const he_mask* mask, uint32_t level,
+                                 const uint32_t* ct_glob_dev, const float* plain_glob_dev,
+                                 float* w_out_dev, void* stream);
+
 /* ---- test / measurement exports (single steps of the calls above) ---------------------- */
 
 /* Slot encoding only: slots_dev float32[n_ct][n] -> m_out_dev int32[n_ct][N],

@@ -92,6 +92,61 @@ def secure_round(p: Params, keys, ws, alpha, runs, seed, fast=True):
     return out
 
 
+# ---- variant: weighing on the client, the server only adds -------------------------------------
+# (Section "Comparison with Other FL Frameworks": "scales each learner's local model parameters
+#  locally rather than weighing ciphertexts on the server"; no ciphertext-scalar product, no rescale.)
+
+def encrypt_ct_weighted(p, keys, w, enc_idx, alpha_i, seed, client_id, ct_index, fast=True):
+    """Client side: slots alpha_i * w (float64 product), encode, encrypt.  Returns (m, ct)."""
+    z = np.float64(alpha_i) * pack_slots(p, w, enc_idx, ct_index)
+    enc = encoder.encode_fft if fast else encoder.encode_def
+    m = enc(z, p.log2_n, p.scale_bits)
+    return m, scheme.encrypt(p, keys, m, seed, client_id, ct_index)
+
+
+def plain_weighted(w, alpha_i):
+    """What a client sends of its plaintext remainder: float32(alpha_i * w), product in float64."""
+    return (np.float64(alpha_i) * np.asarray(w).astype(np.float64)).astype(np.float32)
+
+
+def plain_sum(ws):
+    """Server side of the plaintext remainder: float64 sum in client order, one rounding to float32."""
+    acc = np.zeros(np.asarray(ws[0]).shape, dtype=np.float64)
+    for w in ws:
+        acc = acc + np.asarray(w).astype(np.float64)
+    return acc.astype(np.float32)
+
+
+def decode_ct_level(p, keys, ct_glob, level, fast=True):
+    v = scheme.decrypt(p, keys, ct_glob, level)
+    dec = encoder.decode_fft if fast else encoder.decode_def
+    return dec(np.array([float(x) for x in v], dtype=np.float64), p.log2_n, p.scale_bits)
+
+
+def secure_round_client_weighted(p: Params, keys, ws, alpha, runs, seed, fast=True):
+    """Whole round of the variant for K clients.  Returns the merged float32 global model."""
+    P = np.asarray(ws[0]).shape[0]
+    enc_idx, plain_idx = mask_indices(P, runs)
+    n_ct = n_ciphertexts(p, enc_idx.shape[0])
+    out = np.zeros(P, dtype=np.float32)
+    out[plain_idx] = plain_sum([plain_weighted(np.asarray(w)[plain_idx], a) for w, a in zip(ws, alpha)])
+    for c in range(n_ct):
+        cts = [encrypt_ct_weighted(p, keys, w, enc_idx, a, seed, i, c, fast)[1] for i, (w, a) in enumerate(zip(ws, alpha))]
+        z = decode_ct_level(p, keys, scheme.sum_ciphertexts(p, cts), p.n_limbs, fast)
+        sel = enc_idx[c * p.n_slots:(c + 1) * p.n_slots]
+        out[sel] = z[:sel.shape[0]].astype(np.float32)
+    return out
+
+
+def noise_sigma_client_weighted(p: Params, n_clients: int):
+    """Predicted RMS slot error of the variant: K fresh noises add up unweighted, no rescale term;
+    each client's encoding rounding (variance 1/12 per coefficient) adds up as well."""
+    half_eta = p.cbd_eta / 2.0
+    var_fresh = half_eta * (2.0 / 3.0) * p.N * 2.0 + half_eta
+    var_coeff = n_clients * (var_fresh + 1.0 / 12.0)
+    return float(np.sqrt(p.N * var_coeff / 2.0)) / p.delta
+
+
 def noise_sigma(p: Params, alpha):
     """Predicted RMS slot error of the decoded aggregate against exact FedAvg.
 

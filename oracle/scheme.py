@@ -105,6 +105,16 @@ def aggregate(p: Params, cts, alpha):
     return rescale(p, weighted_sum(p, cts, alpha))
 
 
+def sum_ciphertexts(p: Params, cts):
+    """Weighing-on-the-client variant (Section "Comparison with Other FL Frameworks": learners scale
+    their parameters locally, the server only adds): out[p][j] = sum_i ct_i[p][j] mod q_j, level kept."""
+    acc = np.zeros_like(np.asarray(cts[0], dtype=np.int64))
+    for j, q in enumerate(p.primes):
+        for ct in cts:
+            acc[:, j] = (acc[:, j] + np.asarray(ct, dtype=np.int64)[:, j]) % q
+    return acc
+
+
 def crt_centered(residues, primes):
     """Exact centred lift of (len(primes), N) residues to Python ints in (-Q/2, Q/2]."""
     big_q = 1

@@ -52,6 +52,9 @@ _SIGS = {
                                      C.c_uint64, C.c_uint64, _P, _P, _P]),
     "he_aggregate_finalize": (C.c_int32, [_P, C.c_uint64, C.c_uint64, _P, _P, _P, _P, _P]),
     "he_decrypt_merge": (C.c_int32, [_P, _P, _P, _P, _P, _P, _P]),
+    "he_encrypt_masked_weighted": (C.c_int32, [_P, _P, _P, C.c_uint64, C.c_uint32, C.c_double, _P, _P, _P, _P]),
+    "he_aggregate_sum": (C.c_int32, [_P, C.c_uint32, C.POINTER(_P), C.POINTER(_P), C.c_uint64, C.c_uint64, _P, _P, _P]),
+    "he_decrypt_merge_level": (C.c_int32, [_P, _P, _P, C.c_uint32, _P, _P, _P, _P]),
     "he_debug_encode": (C.c_int32, [_P, _P, C.c_uint64, _P, _P]),
     "he_debug_encrypt_plain": (C.c_int32, [_P, _P, C.c_uint64, C.c_uint32, C.c_uint64, _P, C.c_uint64, _P, _P]),
     "he_debug_decrypt_residues": (C.c_int32, [_P, _P, _P, C.c_uint64, C.c_uint32, _P, _P]),
@@ -199,6 +202,17 @@ def he_encrypt_masked(ctx, keys, mask, seed, client_id, w, ct_out=None, plain_ou
     return ct_out, plain_out
 
 
+def he_encrypt_masked_weighted(ctx, keys, mask, seed, client_id, alpha, w, ct_out=None, plain_out=None):
+    if ct_out is None:
+        ct_out = torch.empty((mask.n_ct, 2, ctx.L, ctx.N), dtype=torch.int32, device=ctx.device)
+    if plain_out is None:
+        plain_out = torch.empty((mask.n_plain,), dtype=torch.float32, device=ctx.device)
+    assert w.numel() == mask.P and ct_out.numel() == mask.n_ct * 2 * ctx.L * ctx.N and plain_out.numel() == mask.n_plain
+    _check(load().he_encrypt_masked_weighted(ctx.h, keys.pk, mask.h, seed, client_id, float(alpha), _ptr(w, torch.float32),
+                                             _ptr(ct_out, torch.int32), _ptr(plain_out, torch.float32), _stream()))
+    return ct_out, plain_out
+
+
 def _ptr_array(tensors, dtype):
     arr = (_P * len(tensors))()
     for i, t in enumerate(tensors):
@@ -221,6 +235,21 @@ def he_aggregate(ctx, alphas, cts, plains, ct_out=None, plain_out=None):
     pp = _ptr_array(plains, torch.float32) if n_plain else None
     _check(load().he_aggregate(ctx.h, K, a, cp, pp, n_ct, n_plain, _ptr(ct_out) if n_ct else None,
                                _ptr(plain_out) if n_plain else None, _stream()))
+    return ct_out, plain_out
+
+
+def he_aggregate_sum(ctx, cts, plains, ct_out=None, plain_out=None):
+    K = len(cts)
+    n_ct = cts[0].shape[0] if cts and cts[0] is not None else 0
+    n_plain = plains[0].numel() if plains and plains[0] is not None else 0
+    if ct_out is None:
+        ct_out = torch.empty((n_ct, 2, ctx.L, ctx.N), dtype=torch.int32, device=ctx.device)
+    if plain_out is None:
+        plain_out = torch.empty((n_plain,), dtype=torch.float32, device=ctx.device)
+    cp = _ptr_array(cts, torch.int32) if n_ct else None
+    pp = _ptr_array(plains, torch.float32) if n_plain else None
+    _check(load().he_aggregate_sum(ctx.h, K, cp, pp, n_ct, n_plain, _ptr(ct_out) if n_ct else None,
+                                   _ptr(plain_out) if n_plain else None, _stream()))
     return ct_out, plain_out
 
 
@@ -264,6 +293,17 @@ def he_decrypt_merge(ctx, keys, mask, ct_glob, plain_glob, w_out=None):
     _check(load().he_decrypt_merge(ctx.h, keys.sk, mask.h, _ptr(ct_glob, torch.int32) if mask.n_ct else None,
                                    _ptr(plain_glob, torch.float32) if mask.n_plain else None,
                                    _ptr(w_out, torch.float32), _stream()))
+    return w_out
+
+
+def he_decrypt_merge_level(ctx, keys, mask, level, ct_glob, plain_glob, w_out=None):
+    if w_out is None:
+        w_out = torch.empty((mask.P,), dtype=torch.float32, device=ctx.device)
+    assert ct_glob.numel() == mask.n_ct * 2 * level * ctx.N
+    assert (plain_glob.numel() if plain_glob is not None else 0) == mask.n_plain
+    _check(load().he_decrypt_merge_level(ctx.h, keys.sk, mask.h, level, _ptr(ct_glob, torch.int32) if mask.n_ct else None,
+                                         _ptr(plain_glob, torch.float32) if mask.n_plain else None,
+                                         _ptr(w_out, torch.float32), _stream()))
     return w_out
 
 

@@ -114,7 +114,7 @@ __device__ __forceinline__ uint64_t run_lookup_in(const uint64_t* __restrict__ s
 // m_k + i m_{k+n} = Delta * zeta^-k * (1/n) * sum_j z_j exp(-2 pi i t_j k / n)
 __global__ void __launch_bounds__(1024)
 k_encode(RingDev rg, MaskDev mk, const float* __restrict__ w, const float* __restrict__ slots_direct,
-         uint64_t first_ct, int32_t* __restrict__ m_out) {
+         uint64_t first_ct, int32_t* __restrict__ m_out, double pre_scale) {
   extern __shared__ double lds_d[];
   const int logn = (int)rg.logN - 1;
   const int n = 1 << logn;
@@ -131,7 +131,7 @@ k_encode(RingDev rg, MaskDev mk, const float* __restrict__ w, const float* __res
       if (t < mk.P_enc) z = (double)w[run_lookup(mk.start, mk.prefix, mk.n_runs, t)];
     }
     const uint32_t pos = rg.perm_enc[j];
-    re[pos] = z;
+    re[pos] = z * pre_scale;  // client-side weighting (1.0 otherwise: exact)
     im[pos] = 0.0;
   }
   __syncthreads();
@@ -190,7 +190,7 @@ template <int LOGN>
 __global__ void __launch_bounds__(FftPlan<LOGN - 2>::NT)
 k_encode_r(RingDev rg, MaskDev mk, const float* __restrict__ w, const float* __restrict__ slots_direct,
            uint64_t first_ct, int32_t* __restrict__ m_out, uint2 key, uint32_t client, int8_t* __restrict__ u_out,
-           int8_t* __restrict__ e0_out, int8_t* __restrict__ e1_out) {
+           int8_t* __restrict__ e0_out, int8_t* __restrict__ e1_out, double pre_scale) {
   constexpr int LOGh = LOGN - 2, h = 1 << LOGh, n = 2 * h, N = 4 * h;
   using P = FftPlan<LOGh>;
   extern __shared__ double lds_d[];
@@ -230,7 +230,7 @@ k_encode_r(RingDev rg, MaskDev mk, const float* __restrict__ w, const float* __r
     }
   }
 #pragma unroll
-  for (int u = 0; u < U; ++u) ((code[u] & 1) ? im : re)[fswz<LOGh>((int)(code[u] >> 1))] = (double)z[u];
+  for (int u = 0; u < U; ++u) ((code[u] & 1) ? im : re)[fswz<LOGh>((int)(code[u] >> 1))] = (double)z[u] * pre_scale;
   __syncthreads();
   const double2* e_tab = rg.fft_e;  // roots of the n-point transform: the h-point one uses every other entry
   auto ldl = [=](int a, double& r, double& i) { r = re[fswz<LOGh>(a)]; i = im[fswz<LOGh>(a)]; };
@@ -781,8 +781,8 @@ __device__ __forceinline__ void stream_store(uint4* p, uint4 v) {
 
 template <int L, bool HAS_ACC, bool FINAL>
 __global__ void __launch_bounds__(256)
-k_aggregate(AggArgs a, AggConst k, uint32_t log_n4, uint64_t n_vec, const uint4* __restrict__ acc_in,
-            uint4* __restrict__ out) {
+k_aggregate(AggArgs a, AggConst k, uint32_t log_n4, uint64_t n_vec, const uint4* acc_in, uint4* out) {
+  // acc_in and out may be the same buffer (in-place accumulation): a thread reads and writes only its own elements.
   const uint64_t gid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (gid >= n_vec) return;
   const uint64_t cp = gid >> log_n4;                 // ciphertext * 2 + poly
@@ -832,8 +832,8 @@ k_aggregate(AggArgs a, AggConst k, uint32_t log_n4, uint64_t n_vec, const uint4*
 // the outputs must be 16-byte aligned); the tail and unaligned calls use VEC = 1.
 template <bool HAS_ACC, bool FINAL, int VEC>
 __global__ void __launch_bounds__(256)
-k_plain_fedavg(PlainArgs a, uint64_t first, uint64_t n_groups, const double* __restrict__ acc_in,
-               double* __restrict__ acc_out, float* __restrict__ out) {
+k_plain_fedavg(PlainArgs a, uint64_t first, uint64_t n_groups, const double* acc_in, double* acc_out, float* out) {
+  // acc_in / acc_out, and out / a client's input, may be the same buffer: a thread reads and writes only its own elements.
   // The product and the sum must round separately (no fused multiply-add), or the result
   // depends on the compiler's contraction choices.
 #pragma clang fp contract(off)
@@ -1130,7 +1130,8 @@ EncScratch carve_enc_scratch(void* ws, uint64_t chunk, size_t N) {
 // Encode n_ct ciphertexts' slots into m_out; when `rnd` is given, also draw their randomness
 // (specialised sizes do it inside the encoder kernel, the generic path with k_sample).
 he_status launch_encode(he_ctx* ctx, const MaskDev& mk, const float* w, const float* slots, uint64_t first_ct,
-                        uint64_t n_ct, int32_t* m_out, const EncScratch* rnd, uint64_t seed, uint32_t client, hipStream_t st) {
+                        uint64_t n_ct, int32_t* m_out, const EncScratch* rnd, uint64_t seed, uint32_t client, hipStream_t st,
+                        double pre_scale = 1.0) {
   const RingDev& rg = ctx->ring;
   const uint32_t n = rg.N / 2;
   const uint2 key = make_uint2((uint32_t)seed, (uint32_t)(seed >> 32));
@@ -1142,14 +1143,15 @@ he_status launch_encode(he_ctx* ctx, const MaskDev& mk, const float* w, const fl
     KernelTimer timer_(ctx, KID_ENCODE, st);
     if (rg.logN == 14) {
       hipLaunchKernelGGL(k_encode_r<14>, dim3((uint32_t)n_ct), dim3(FftPlan<12>::NT), static_fft_lds_bytes(12), st, rg, mk, w, slots,
-                         first_ct, m_out, key, client, u, e0, e1);
+                         first_ct, m_out, key, client, u, e0, e1, pre_scale);
       sampled = true;
     } else if (rg.logN == 13) {
       hipLaunchKernelGGL(k_encode_r<13>, dim3((uint32_t)n_ct), dim3(FftPlan<11>::NT), static_fft_lds_bytes(11), st, rg, mk, w, slots,
-                         first_ct, m_out, key, client, u, e0, e1);
+                         first_ct, m_out, key, client, u, e0, e1, pre_scale);
       sampled = true;
     } else {
-      hipLaunchKernelGGL(k_encode, dim3((uint32_t)n_ct), dim3(fft_threads(n)), fft_lds_bytes(n), st, rg, mk, w, slots, first_ct, m_out);
+      hipLaunchKernelGGL(k_encode, dim3((uint32_t)n_ct), dim3(fft_threads(n)), fft_lds_bytes(n), st, rg, mk, w, slots, first_ct, m_out,
+                         pre_scale);
     }
   }
   HIP_TRY(hipGetLastError());
@@ -1685,8 +1687,9 @@ uint64_t he_n_ct(const he_ctx* ctx, const he_mask* mask) {
 
 // ---- client: encrypt -------------------------------------------------------------------
 
-he_status he_encrypt_masked(he_ctx* ctx, const he_pk* pk, const he_mask* mask, uint64_t seed, uint32_t client_id,
-                            const float* w_dev, uint32_t* ct_out_dev, float* plain_out_dev, void* stream) {
+static he_status encrypt_masked_impl(he_ctx* ctx, const he_pk* pk, const he_mask* mask, uint64_t seed, uint32_t client_id,
+                                     double pre_scale, const float* w_dev, uint32_t* ct_out_dev, float* plain_out_dev,
+                                     void* stream) {
   he_status s = check_ctx(ctx);
   if (s != HE_OK) return s;
   if (!pk || !mask || pk->ctx != ctx || mask->ctx != ctx) return fail(HE_ERR_INVALID_ARG, "key/mask missing or from another context");
@@ -1705,17 +1708,39 @@ he_status he_encrypt_masked(he_ctx* ctx, const he_pk* pk, const he_mask* mask, u
   const EncScratch sc = carve_enc_scratch(ctx->ws, chunk, N);
   for (uint64_t c0 = 0; c0 < n_ct; c0 += chunk) {
     const uint64_t cn = std::min<uint64_t>(chunk, n_ct - c0);
-    s = launch_encode(ctx, mk, w_dev, nullptr, c0, cn, sc.m, &sc, seed, client_id, st);
+    s = launch_encode(ctx, mk, w_dev, nullptr, c0, cn, sc.m, &sc, seed, client_id, st, pre_scale);
     if (s != HE_OK) return s;
     s = launch_encrypt(ctx, pk, cn, sc.m, sc, ct_out_dev + c0 * 2 * rg.L * N, st);
     if (s != HE_OK) return s;
   }
   if (n_plain) {
-    KernelTimer timer_(ctx, KID_PLAIN_MOVE, st);
-    launch_plain_move<false>(mk, w_dev, plain_out_dev, st);
-    HIP_TRY(hipGetLastError());
+    {
+      KernelTimer timer_(ctx, KID_PLAIN_MOVE, st);
+      launch_plain_move<false>(mk, w_dev, plain_out_dev, st);
+      HIP_TRY(hipGetLastError());
+    }
+    if (pre_scale != 1.0) {  // weigh the compacted remainder in place: float32(alpha * x), product in float64
+      PlainArgs pa{};
+      pa.K = 1;
+      pa.w[0] = plain_out_dev;
+      pa.alpha[0] = pre_scale;
+      s = launch_plain(ctx, false, true, pa, n_plain, nullptr, nullptr, plain_out_dev, st);
+      if (s != HE_OK) return s;
+    }
   }
   return HE_OK;
+}
+
+he_status he_encrypt_masked(he_ctx* ctx, const he_pk* pk, const he_mask* mask, uint64_t seed, uint32_t client_id,
+                            const float* w_dev, uint32_t* ct_out_dev, float* plain_out_dev, void* stream) {
+  return encrypt_masked_impl(ctx, pk, mask, seed, client_id, 1.0, w_dev, ct_out_dev, plain_out_dev, stream);
+}
+
+he_status he_encrypt_masked_weighted(he_ctx* ctx, const he_pk* pk, const he_mask* mask, uint64_t seed, uint32_t client_id,
+                                     double alpha, const float* w_dev, uint32_t* ct_out_dev, float* plain_out_dev,
+                                     void* stream) {
+  if (!(alpha > 0.0) || !(alpha <= 1.0)) return fail(HE_ERR_INVALID_ARG, "aggregation weight must be in (0, 1]");
+  return encrypt_masked_impl(ctx, pk, mask, seed, client_id, alpha, w_dev, ct_out_dev, plain_out_dev, stream);
 }
 
 // ---- server: aggregate -----------------------------------------------------------------
@@ -1746,6 +1771,45 @@ he_status he_aggregate(he_ctx* ctx, uint32_t K, const double* alpha_host, const 
   }
   return aggregate_impl(ctx, K, alpha_host, w, ct_in_dev, plain_in_dev, n_ct, n_plain, false, true, acc_ct, acc_plain,
                         ct_out_dev, plain_out_dev, st);
+}
+
+he_status he_aggregate_sum(he_ctx* ctx, uint32_t K, const uint32_t* const* ct_in_dev, const float* const* plain_in_dev,
+                           uint64_t n_ct, uint64_t n_plain, uint32_t* ct_out_dev, float* plain_out_dev, void* stream) {
+  he_status s = check_ctx(ctx);
+  if (s != HE_OK) return s;
+  if (K == 0 || K > HE_MAX_CLIENTS_PER_CALL) return fail(HE_ERR_INVALID_ARG, "K must be in 1..HE_MAX_CLIENTS_PER_CALL");
+  if ((n_ct && (!ct_in_dev || !ct_out_dev)) || (n_plain && (!plain_in_dev || !plain_out_dev)))
+    return fail(HE_ERR_INVALID_ARG, "null argument");
+  for (uint32_t i = 0; i < K; ++i)
+    if ((n_ct && !ct_in_dev[i]) || (n_plain && !plain_in_dev[i])) return fail(HE_ERR_INVALID_ARG, "null client buffer");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const uint32_t L = ctx->ring.L;
+  double* acc_plain = nullptr;
+  if (K > (uint32_t)kAggClients && n_plain) {  // float64 partial sums of the plaintext part between launches
+    s = ensure_ws(ctx, n_plain * sizeof(double));
+    if (s != HE_OK) return s;
+    acc_plain = static_cast<double*>(ctx->ws);
+  }
+  uint32_t done = 0;
+  do {  // unit weights, no rescale: the sum of residues in all L limbs IS the result (accumulated in place)
+    const uint32_t kc = std::min<uint32_t>(kAggClients, K - done);
+    const bool first = done == 0, last = done + kc == K;
+    AggArgs a{};
+    PlainArgs pa{};
+    a.K = pa.K = kc;
+    for (uint32_t i = 0; i < kc; ++i) {
+      a.ct[i] = n_ct ? ct_in_dev[done + i] : nullptr;
+      for (uint32_t j = 0; j < L; ++j) a.w[i][j] = 1;
+      pa.w[i] = n_plain ? plain_in_dev[done + i] : nullptr;
+      pa.alpha[i] = 1.0;
+    }
+    s = launch_agg(ctx, !first, false, a, n_ct, ct_out_dev, ct_out_dev, st);
+    if (s != HE_OK) return s;
+    s = launch_plain(ctx, !first, last, pa, n_plain, acc_plain, acc_plain, plain_out_dev, st);
+    if (s != HE_OK) return s;
+    done += kc;
+  } while (done < K);
+  return HE_OK;
 }
 
 he_status he_aggregate_begin(he_ctx* ctx, uint64_t n_ct, uint64_t n_plain, uint32_t* acc_ct_dev, double* acc_plain_dev,
@@ -1800,8 +1864,8 @@ he_status he_aggregate_finalize(he_ctx* ctx, uint64_t n_ct, uint64_t n_plain, co
 
 // ---- client: decrypt + merge -----------------------------------------------------------
 
-he_status he_decrypt_merge(he_ctx* ctx, const he_sk* sk, const he_mask* mask, const uint32_t* ct_glob_dev,
-                           const float* plain_glob_dev, float* w_out_dev, void* stream) {
+static he_status decrypt_merge_impl(he_ctx* ctx, const he_sk* sk, const he_mask* mask, uint32_t level,
+                                    const uint32_t* ct_glob_dev, const float* plain_glob_dev, float* w_out_dev, void* stream) {
   he_status s = check_ctx(ctx);
   if (s != HE_OK) return s;
   if (!sk || !mask || sk->ctx != ctx || mask->ctx != ctx) return fail(HE_ERR_INVALID_ARG, "key/mask missing or from another context");
@@ -1810,7 +1874,7 @@ he_status he_decrypt_merge(he_ctx* ctx, const he_sk* sk, const he_mask* mask, co
   if ((mk.P && !w_out_dev) || (n_ct && !ct_glob_dev) || (n_plain && !plain_glob_dev)) return fail(HE_ERR_INVALID_ARG, "null data pointer");
   hipStream_t st = static_cast<hipStream_t>(stream);
   const RingDev& rg = ctx->ring;
-  const uint32_t level = rg.L - 1;
+  if (level < 1 || level > rg.L) return fail(HE_ERR_LEVEL, "level must be in 1..L");
   const uint64_t chunk = std::min<uint64_t>(kCtChunk, n_ct);
   const size_t N = rg.N;
   if (chunk) {
@@ -1831,6 +1895,17 @@ he_status he_decrypt_merge(he_ctx* ctx, const he_sk* sk, const he_mask* mask, co
     HIP_TRY(hipGetLastError());
   }
   return HE_OK;
+}
+
+he_status he_decrypt_merge(he_ctx* ctx, const he_sk* sk, const he_mask* mask, const uint32_t* ct_glob_dev,
+                           const float* plain_glob_dev, float* w_out_dev, void* stream) {
+  if (!ctx) return fail(HE_ERR_INVALID_ARG, "context is null");
+  return decrypt_merge_impl(ctx, sk, mask, ctx->ring.L - 1, ct_glob_dev, plain_glob_dev, w_out_dev, stream);
+}
+
+he_status he_decrypt_merge_level(he_ctx* ctx, const he_sk* sk, const he_mask* mask, uint32_t level,
+                                 const uint32_t* ct_glob_dev, const float* plain_glob_dev, float* w_out_dev, void* stream) {
+  return decrypt_merge_impl(ctx, sk, mask, level, ct_glob_dev, plain_glob_dev, w_out_dev, stream);
 }
 
 // ---- test / measurement exports ---------------------------------------------------------

@@ -254,6 +254,58 @@ def test_round_small(he, log2_n, limbs, case):
     assert torch.equal(ct_again, cts[0])
 
 
+@pytest.mark.parametrize("log2_n,limbs,K", [(10, 2, 3), (13, 2, 5), (14, 3, 8), (10, 3, 70)])
+def test_client_weighted_variant(he, log2_n, limbs, K):
+    """Weighing on the client, the server only adds: every step against the oracle."""
+    ctx, keys, p, okeys = _setup(he, log2_n, limbs)
+    n = p.n_slots
+    P = 2 * n + 777
+    runs = [(5, n + 100), (n + 300, n // 2)]
+    mask = he.he_mask_create(ctx, P, [r[0] for r in runs], [r[1] for r in runs])
+    enc_idx, plain_idx = ofed.mask_indices(P, runs)
+    rs = np.random.default_rng(8)
+    ws = [rs.normal(0, 0.05, P).astype(np.float32) for _ in range(K)]
+    counts = rs.integers(100, 1001, K)
+    alpha = counts / counts.sum()
+    cts, plains = [], []
+    for i, w in enumerate(ws):
+        ct, pl = he.he_encrypt_masked_weighted(ctx, keys, mask, SEED, i, alpha[i], _dev(w))
+        cts.append(ct)
+        plains.append(pl)
+        assert np.array_equal(_np(pl), ofed.plain_weighted(w[plain_idx], alpha[i]))
+    ct_g, pl_g = he.he_aggregate_sum(ctx, cts, plains)
+    out = _np(he.he_decrypt_merge_level(ctx, keys, mask, limbs, ct_g, pl_g))
+    assert np.array_equal(_np(pl_g), ofed.plain_sum([_np(x) for x in plains]))
+    ct_gn = _np(ct_g).astype(np.int64)
+    expect = np.zeros(P, dtype=np.float32)
+    expect[plain_idx] = _np(pl_g)
+    checked_clients = range(K) if K <= 8 else [0, K - 1]
+    for c in range(mask.n_ct):
+        for i in checked_clients:
+            z = np.float64(alpha[i]) * ofed.pack_slots(p, ws[i], enc_idx, c)
+            ref = osch.encrypt(p, okeys, oenc.encode_fft(z, log2_n, 30), SEED, i, c)
+            ct_i = _np(cts[i][c]).astype(np.int64)
+            # c1 does not involve the plaintext: bit-exact.  c0 differs from the oracle's by the encoder's
+            # +-1 tolerance only, the same small integer in every limb.
+            assert np.array_equal(ct_i[1], ref[1])
+            d0 = None
+            for j, q in enumerate(p.primes):
+                dj = (ct_i[0, j] - ref[0, j]) % q
+                dj = np.where(dj > q // 2, dj - q, dj)
+                assert np.abs(dj).max() <= 1 and (dj != 0).mean() < 1e-3
+                assert d0 is None or np.array_equal(dj, d0)
+                d0 = dj
+        agg = osch.sum_ciphertexts(p, [_np(cts[i][c]).astype(np.int64) for i in range(K)])
+        assert np.array_equal(ct_gn[c], agg)
+        zdec = ofed.decode_ct_level(p, okeys, agg, limbs)
+        sel = enc_idx[c * n:(c + 1) * n]
+        expect[sel] = zdec[:len(sel)].astype(np.float32)
+    assert np.array_equal(out[plain_idx], expect[plain_idx])
+    assert np.abs(out.astype(np.float64) - expect.astype(np.float64)).max() <= 1e-6
+    ref = ofed.fedavg_float64(ws, alpha)
+    assert np.abs(out[enc_idx] - ref[enc_idx]).max() < 16 * ofed.noise_sigma_client_weighted(p, K)
+
+
 def test_mask_from_bytes_and_errors(he):
     ctx, keys, p, _ = _setup(he, 10, 3)
     P = 5000

@@ -164,3 +164,54 @@ def test_noiseless_mode_is_tight():
     sig = np.sqrt(p.N * (1 + 2 * p.N / 3) / 24.0) / p.delta
     err = out.astype(np.float64) - ref
     assert np.abs(err).max() < 8 * sig + 2 ** -24 * 0.3 and np.sqrt((err ** 2).mean()) < 1.5 * sig + 2e-8
+
+
+# ---- variant: weighing on the client, the server only adds (Section "Comparison with Other FL Frameworks") ----
+
+def test_ciphertext_sum_is_the_sum_of_plaintexts(ctx):
+    """Decrypting the sum gives exactly the sum of what each ciphertext decrypts to (no wrap: << Q/2)."""
+    p, keys = ctx
+    rs = np.random.default_rng(11)
+    K = 5
+    ms = [rs.integers(-(1 << 27), 1 << 27, p.N) for _ in range(K)]
+    cts = [scheme.encrypt(p, keys, m, 123, i, 3) for i, m in enumerate(ms)]
+    each = [np.array(scheme.decrypt(p, keys, ct, p.n_limbs), dtype=object) for ct in cts]
+    got = np.array(scheme.decrypt(p, keys, scheme.sum_ciphertexts(p, cts), p.n_limbs), dtype=object)
+    assert np.array_equal(got, sum(each))
+    # one client: the sum is the ciphertext itself
+    assert np.array_equal(scheme.sum_ciphertexts(p, [cts[0]]), cts[0])
+    # residues stay canonical even for the largest inputs
+    big = np.stack([np.stack([np.full(p.N, q - 1, dtype=np.int64) for q in p.primes])] * 2)
+    s3 = scheme.sum_ciphertexts(p, [big, big, big])
+    for j, q in enumerate(p.primes):
+        assert np.all(s3[:, j] == (3 * (q - 1)) % q)
+
+
+@pytest.mark.parametrize("log2_n,limbs,K,std", [(13, 2, 3, 0.05), (14, 3, 8, 0.02)])
+def test_client_weighted_round_against_float64_fedavg(log2_n, limbs, K, std):
+    p = Params(log2_n, limbs)
+    keys = scheme.keygen(p, 99)
+    rs = np.random.default_rng(4)
+    P = 3 * p.n_slots + 1234
+    ws = [rs.normal(0, std, P).astype(np.float32) for _ in range(K)]
+    counts = rs.integers(100, 1001, K)
+    alpha = counts / counts.sum()
+    runs = [(10, 2 * p.n_slots), (2 * p.n_slots + 500, 777)]
+    out = fedavg.secure_round_client_weighted(p, keys, ws, alpha, runs, seed=31337)
+    ref = fedavg.fedavg_float64(ws, alpha)
+    enc_idx, plain_idx = fedavg.mask_indices(P, runs)
+    # plaintext part: every client rounds alpha*w to float32 first, so it matches FedAvg to float32 accuracy only
+    assert np.abs(out[plain_idx].astype(np.float64) - ref[plain_idx]).max() < K * 2.0 ** -24 * np.abs(ref[plain_idx]).max() + 1e-9
+    err = out[enc_idx].astype(np.float64) - ref[enc_idx]
+    sigma = fedavg.noise_sigma_client_weighted(p, K)
+    rms = float(np.sqrt((err ** 2).mean()))
+    assert 0.7 * sigma < rms < 1.4 * sigma and np.abs(err).max() < 16 * sigma
+    # the K unweighted noises make this variant noisier than weighing on the server
+    assert sigma > 1.5 * fedavg.noise_sigma(Params(log2_n, limbs + 1), alpha)
+
+
+def test_client_weighted_plain_part_exact_cases():
+    w = np.array([0.1, -0.25, 3.0, 1e-8], dtype=np.float32)
+    assert np.array_equal(fedavg.plain_weighted(w, 1.0), w)
+    assert np.array_equal(fedavg.plain_weighted(w, 0.5), (w.astype(np.float64) / 2).astype(np.float32))
+    assert np.array_equal(fedavg.plain_sum([w, w]), (2 * w.astype(np.float64)).astype(np.float32))
