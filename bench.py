@@ -173,6 +173,28 @@ def crypto_param_sweep(he, torch, P=1_663_370, K=3, reps=3):
     return {"params": P, "clients": K, "rows": rows}
 
 
+def mask_select_bench(he, ctx, torch, sizes=(25_600_000, 110_000_000, 1_300_000_000), ratio=0.1, reps=3):
+    """Select(global privacy map, p) on model-sized maps (layer-structured synthetic sensitivities): wall time of the
+    whole set-up call (three histogram passes, mark, run extraction, temporaries, the run list's trip to the host)."""
+    rows = []
+    for P in sizes:
+        g = torch.Generator(device="cuda").manual_seed(P % 1000)
+        sens = torch.rand(P // 4096 + 1, generator=g, device="cuda").repeat_interleave(4096)[:P].contiguous()
+        sens += 0.05 * torch.rand(P, generator=g, device="cuda")
+        he.he_mask_select_top(ctx, sens, ratio).close()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            m = he.he_mask_select_top(ctx, sens, ratio)
+            n_runs = int(he.load().he_mask_n_runs(m.h))
+            m.close()
+        ms = (time.perf_counter() - t0) * 1e3 / reps
+        alg = P * (3 * 4 + 4 + 1 + 2)      # three histogram passes and the mark pass read 4 B, mark writes 1 B, two run passes read 1 B
+        rows.append({"params": P, "ratio": ratio, "runs": n_runs, "ms": ms, "algorithmic_GBps": alg / (ms * 1e-3) / 1e9})
+        del sens
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -184,6 +206,8 @@ def main():
                     help="client_weighted: clients encode alpha_i * W_i, the server only adds ciphertexts (no rescale), one limb fewer")
     ap.add_argument("--param-sweep", action="store_true",
                     help="also run packing batch 1024..8192 x scaling bits 20/30 on a 1.66M-parameter vector, 3 clients")
+    ap.add_argument("--select-bench", action="store_true",
+                    help="also time the encryption-mask selection (top-p of a sensitivity map) on 25.6M / 110M / 1.3B entries")
     ap.add_argument("--k-sweep", action="store_true",
                     help="also time he_aggregate alone for K = 3 ... 200 clients (server cost against the number of clients)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -293,6 +317,7 @@ def main():
 
     k_sweep = aggregate_k_sweep(he, ctx, torch) if args.k_sweep else None
     param_sweep = crypto_param_sweep(he, torch) if args.param_sweep else None
+    select_rows = mask_select_bench(he, ctx, torch) if args.select_bench else None
 
     # sanity: the decoded aggregate is FedAvg up to the CKKS noise (not part of the timing)
     ref = sum(float(a) * x.double() for a, x in zip(alpha, ws))
@@ -340,6 +365,8 @@ def main():
         res["aggregate_k_sweep"] = k_sweep
     if param_sweep is not None:
         res["crypto_param_sweep"] = param_sweep
+    if select_rows is not None:
+        res["mask_select"] = select_rows
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, ws_host, alpha, runs, client_weighted=client_weighted)
     print(json.dumps(res))

@@ -40,6 +40,9 @@ _SIGS = {
     "he_sk_destroy": (None, [_P]),
     "he_mask_create": (C.c_int32, [_P, C.c_uint64, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.c_uint64, C.POINTER(_P)]),
     "he_mask_from_bytes": (C.c_int32, [_P, C.c_uint64, _P, C.POINTER(_P), _P]),
+    "he_mask_select_top": (C.c_int32, [_P, C.c_uint64, _P, C.c_double, C.POINTER(_P), _P]),
+    "he_mask_n_runs": (C.c_uint64, [_P]),
+    "he_mask_runs": (C.c_int32, [_P, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]),
     "he_mask_destroy": (None, [_P]),
     "he_mask_n_params": (C.c_uint64, [_P]),
     "he_mask_n_enc": (C.c_uint64, [_P]),
@@ -188,6 +191,20 @@ def he_mask_from_bytes(ctx, mask_bytes):
     h = _P()
     _check(load().he_mask_from_bytes(ctx.h, mask_bytes.numel(), _ptr(mask_bytes, torch.uint8), C.byref(h), _stream()))
     return Mask(ctx, h)
+
+
+def he_mask_select_top(ctx, sens, ratio):
+    h = _P()
+    _check(load().he_mask_select_top(ctx.h, sens.numel(), _ptr(sens, torch.float32), float(ratio), C.byref(h), _stream()))
+    return Mask(ctx, h)
+
+
+def he_mask_runs(mask):
+    """(starts, lens) of the mask's run list as Python lists."""
+    n = load().he_mask_n_runs(mask.h)
+    a, b = (C.c_uint64 * max(n, 1))(), (C.c_uint64 * max(n, 1))()
+    _check(load().he_mask_runs(mask.h, a, b))
+    return list(a[:n]), list(b[:n])
 
 
 def he_encrypt_masked(ctx, keys, mask, seed, client_id, w, ct_out=None, plain_out=None):

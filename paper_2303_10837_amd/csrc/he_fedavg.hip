@@ -15,6 +15,7 @@
 #include "he_host_tables.hpp"
 #include "he_fft_static.hpp"
 #include "he_ntt_static.hpp"
+#include "he_select.hpp"
 
 using namespace he;
 
@@ -1011,6 +1012,7 @@ struct he_mask {
   he_ctx* ctx;
   MaskDev dev{};
   void* dev_block = nullptr;
+  std::vector<uint64_t> starts, lens;  // host copy of the run list
 };
 
 namespace {
@@ -1642,39 +1644,152 @@ he_status he_mask_create(he_ctx* ctx, uint64_t P, const uint64_t* starts, const 
   mk->dev.n_cruns = (uint32_t)cs_v.size();
   mk->dev.P = P;
   mk->dev.P_enc = packed;
+  mk->starts.assign(starts, starts + n_runs);
+  mk->lens.assign(lens, lens + n_runs);
   *out = mk;
   return HE_OK;
+}
+
+// Run list of a device byte mask (non-zero = selected), extracted on the GPU: per-chunk counts of
+// run starts and ends, an exclusive scan, an emit pass; only the runs themselves travel to the host.
+static he_status mask_from_device_bytes(he_ctx* ctx, uint64_t P, const uint8_t* mask_dev, he_mask** out, hipStream_t st) {
+  using namespace he_sel;
+  if (P == 0) return he_mask_create(ctx, 0, nullptr, nullptr, 0, out);
+  const uint64_t n_chunks = (P + kChunk - 1) / kChunk;
+  if (n_chunks > 0x7FFFFFFFull) return fail(HE_ERR_INVALID_ARG, "vector too long");
+  char* tmp = nullptr;
+  uint64_t* runs_dev = nullptr;
+  const size_t cnt_bytes = ((n_chunks * sizeof(uint32_t) + 255) / 256) * 256;
+  const size_t off_bytes = (((n_chunks + 1) * sizeof(uint64_t) + 255) / 256) * 256;
+  auto cleanup = [&]() {
+    if (tmp) (void)hipFree(tmp);
+    if (runs_dev) (void)hipFree(runs_dev);
+  };
+#define MK_TRY(expr)                                                                 \
+  do {                                                                               \
+    hipError_t e_ = (expr);                                                          \
+    if (e_ != hipSuccess) {                                                          \
+      cleanup();                                                                     \
+      return fail(e_ == hipErrorOutOfMemory ? HE_ERR_NOMEM : HE_ERR_HIP, std::string(#expr) + ": " + hipGetErrorString(e_)); \
+    }                                                                                \
+  } while (0)
+  MK_TRY(hipMalloc(&tmp, 2 * cnt_bytes + 2 * off_bytes));
+  uint32_t* n_start = reinterpret_cast<uint32_t*>(tmp);
+  uint32_t* n_end = reinterpret_cast<uint32_t*>(tmp + cnt_bytes);
+  uint64_t* off_start = reinterpret_cast<uint64_t*>(tmp + 2 * cnt_bytes);
+  uint64_t* off_end = reinterpret_cast<uint64_t*>(tmp + 2 * cnt_bytes + off_bytes);
+  hipLaunchKernelGGL(k_runs<false>, dim3((uint32_t)n_chunks), dim3(kThreads), 0, st, mask_dev, P, n_start, n_end, nullptr, nullptr,
+                     nullptr, nullptr);
+  hipLaunchKernelGGL(k_scan_counts, dim3(1), dim3(1024), 0, st, n_start, n_chunks, off_start);
+  hipLaunchKernelGGL(k_scan_counts, dim3(1), dim3(1024), 0, st, n_end, n_chunks, off_end);
+  MK_TRY(hipGetLastError());
+  uint64_t totals[2] = {0, 0};
+  MK_TRY(hipMemcpyAsync(&totals[0], off_start + n_chunks, sizeof(uint64_t), hipMemcpyDeviceToHost, st));
+  MK_TRY(hipMemcpyAsync(&totals[1], off_end + n_chunks, sizeof(uint64_t), hipMemcpyDeviceToHost, st));
+  MK_TRY(hipStreamSynchronize(st));
+  const uint64_t R = totals[0];
+  if (totals[1] != R) {
+    cleanup();
+    return fail(HE_ERR_HIP, "run extraction: starts and ends disagree");
+  }
+  std::vector<uint64_t> starts(R), lens(R);
+  if (R) {
+    MK_TRY(hipMalloc(&runs_dev, 2 * R * sizeof(uint64_t)));
+    hipLaunchKernelGGL(k_runs<true>, dim3((uint32_t)n_chunks), dim3(kThreads), 0, st, mask_dev, P, nullptr, nullptr, off_start, off_end,
+                       runs_dev, runs_dev + R);
+    MK_TRY(hipGetLastError());
+    MK_TRY(hipMemcpyAsync(starts.data(), runs_dev, R * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
+    MK_TRY(hipMemcpyAsync(lens.data(), runs_dev + R, R * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
+    MK_TRY(hipStreamSynchronize(st));
+    for (uint64_t r = 0; r < R; ++r) lens[r] -= starts[r];  // ends -> lengths
+  }
+  cleanup();
+#undef MK_TRY
+  return he_mask_create(ctx, P, starts.data(), lens.data(), R, out);
 }
 
 he_status he_mask_from_bytes(he_ctx* ctx, uint64_t P, const uint8_t* mask_dev, he_mask** out, void* stream) {
   he_status s = check_ctx(ctx);
   if (s != HE_OK) return s;
   if (!out || (P && !mask_dev)) return fail(HE_ERR_INVALID_ARG, "null argument");
-  std::vector<uint8_t> host(P);
+  return mask_from_device_bytes(ctx, P, mask_dev, out, static_cast<hipStream_t>(stream));
+}
+
+he_status he_mask_select_top(he_ctx* ctx, uint64_t P, const float* s_dev, double ratio, he_mask** out, void* stream) {
+  using namespace he_sel;
+  he_status s = check_ctx(ctx);
+  if (s != HE_OK) return s;
+  if (!out || (P && !s_dev)) return fail(HE_ERR_INVALID_ARG, "null argument");
+  if (!(ratio >= 0.0) || !(ratio <= 1.0)) return fail(HE_ERR_INVALID_ARG, "ratio must be in [0, 1]");
+  if (P >= (1ull << 40)) return fail(HE_ERR_INVALID_ARG, "vector too long");
+  const uint64_t k = (uint64_t)std::nearbyint(ratio * (double)P);  // ties to even, as everywhere else
+  if (k == 0) return he_mask_create(ctx, P, nullptr, nullptr, 0, out);
+  if (k >= P) {
+    const uint64_t zero = 0;
+    return he_mask_create(ctx, P, &zero, &P, 1, out);
+  }
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (P) {
-    HIP_TRY(hipMemcpyAsync(host.data(), mask_dev, P, hipMemcpyDeviceToHost, st));
-    HIP_TRY(hipStreamSynchronize(st));
+  const uint64_t n_chunks = (P + kChunk - 1) / kChunk;
+  if (n_chunks > 0x7FFFFFFFull) return fail(HE_ERR_INVALID_ARG, "vector too long");
+  constexpr size_t kHistBytes = 3 * 2048 * sizeof(unsigned long long);
+  const size_t cnt_bytes = ((n_chunks * sizeof(uint32_t) + 255) / 256) * 256;
+  const size_t off_bytes = (((n_chunks + 1) * sizeof(uint64_t) + 255) / 256) * 256;
+  const size_t mask_bytes = ((P + 255) / 256) * 256;
+  char* tmp = nullptr;
+  HIP_TRY(hipMalloc(&tmp, 256 + kHistBytes + cnt_bytes + off_bytes + mask_bytes));
+  SelState* state = reinterpret_cast<SelState*>(tmp);
+  unsigned long long* hist = reinterpret_cast<unsigned long long*>(tmp + 256);
+  uint32_t* eq_count = reinterpret_cast<uint32_t*>(tmp + 256 + kHistBytes);
+  uint64_t* eq_off = reinterpret_cast<uint64_t*>(tmp + 256 + kHistBytes + cnt_bytes);
+  uint8_t* mask_dev = reinterpret_cast<uint8_t*>(tmp + 256 + kHistBytes + cnt_bytes + off_bytes);
+#define SEL_TRY(expr)                                                                \
+  do {                                                                               \
+    hipError_t e_ = (expr);                                                          \
+    if (e_ != hipSuccess) {                                                          \
+      (void)hipFree(tmp);                                                            \
+      return fail(HE_ERR_HIP, std::string(#expr) + ": " + hipGetErrorString(e_));    \
+    }                                                                                \
+  } while (0)
+  SelState init{0u, 0u, k, 0u};
+  SEL_TRY(hipMemcpyAsync(state, &init, sizeof(init), hipMemcpyHostToDevice, st));
+  hipLaunchKernelGGL(k_fill_u32, dim3(24), dim3(256), 0, st, reinterpret_cast<uint32_t*>(hist), (uint64_t)(kHistBytes / 4), 0u);
+  const dim3 hgrid((uint32_t)std::min<uint64_t>(8192, (P + kThreads - 1) / kThreads));
+  hipLaunchKernelGGL((k_hist<21, 11>), hgrid, dim3(kThreads), 0, st, s_dev, P, state, 0u, hist);
+  hipLaunchKernelGGL((k_pick<21, 11>), dim3(1), dim3(64), 0, st, hist, state);
+  hipLaunchKernelGGL((k_hist<10, 11>), hgrid, dim3(kThreads), 0, st, s_dev, P, state, 0xFFE00000u, hist + 2048);
+  hipLaunchKernelGGL((k_pick<10, 11>), dim3(1), dim3(64), 0, st, hist + 2048, state);
+  hipLaunchKernelGGL((k_hist<0, 10>), hgrid, dim3(kThreads), 0, st, s_dev, P, state, 0xFFFFFC00u, hist + 4096);
+  hipLaunchKernelGGL((k_pick<0, 10>), dim3(1), dim3(64), 0, st, hist + 4096, state);
+  SEL_TRY(hipGetLastError());
+  SelState fin{};
+  SEL_TRY(hipMemcpyAsync(&fin, state, sizeof(fin), hipMemcpyDeviceToHost, st));
+  SEL_TRY(hipStreamSynchronize(st));
+  const bool rank_ties = fin.k_rem < fin.cnt_eq;  // only some of the elements equal to the threshold are taken
+  if (rank_ties) {
+    hipLaunchKernelGGL(k_count_eq, dim3((uint32_t)n_chunks), dim3(kThreads), 0, st, s_dev, P, state, eq_count);
+    hipLaunchKernelGGL(k_scan_counts, dim3(1), dim3(1024), 0, st, eq_count, n_chunks, eq_off);
   }
-  std::vector<uint64_t> starts, lens;
-  uint64_t i = 0;
-  while (i < P) {
-    if (!host[i]) {
-      ++i;
-      continue;
-    }
-    uint64_t b = i;
-    while (i < P && host[i]) ++i;
-    starts.push_back(b);
-    lens.push_back(i - b);
-  }
-  return he_mask_create(ctx, P, starts.data(), lens.data(), starts.size(), out);
+  hipLaunchKernelGGL(k_mark, dim3((uint32_t)n_chunks), dim3(kThreads), 0, st, s_dev, P, state, rank_ties ? eq_off : nullptr, mask_dev);
+  SEL_TRY(hipGetLastError());
+#undef SEL_TRY
+  s = mask_from_device_bytes(ctx, P, mask_dev, out, st);  // synchronises the stream before it returns
+  (void)hipFree(tmp);
+  return s;
 }
 
 void he_mask_destroy(he_mask* mask) {
   if (!mask) return;
   if (mask->dev_block) (void)hipFree(mask->dev_block);
   delete mask;
+}
+
+uint64_t he_mask_n_runs(const he_mask* mask) { return mask ? mask->starts.size() : 0; }
+
+he_status he_mask_runs(const he_mask* mask, uint64_t* starts_host, uint64_t* lens_host) {
+  if (!mask || ((!starts_host || !lens_host) && !mask->starts.empty())) return fail(HE_ERR_INVALID_ARG, "null argument");
+  std::copy(mask->starts.begin(), mask->starts.end(), starts_host);
+  std::copy(mask->lens.begin(), mask->lens.end(), lens_host);
+  return HE_OK;
 }
 
 uint64_t he_mask_n_params(const he_mask* mask) { return mask ? mask->dev.P : 0; }
