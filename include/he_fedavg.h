@@ -28,6 +28,8 @@
  *    "packing batch size").  Modulus chain q_0 > ... > q_{L-1}, primes < 2^31, q = 1 mod 2N.
  *  - Ciphertext layout: uint32 [n_ct][2][level][N], coefficient domain, residues in [0,q_j),
  *    poly 0 = c0, poly 1 = c1; a fresh ciphertext has level L, an aggregated one L-1.
+ *    Ciphertext buffers must be 16-byte aligned (HE_ERR_INVALID_ARG otherwise).  While
+ *    he_encrypt_masked runs, rows of its output buffer hold intermediate values.
  *  - Masked parameters are packed in parameter order, n per ciphertext, the last ciphertext
  *    zero padded (a vector shorter than the packing batch still takes a whole ciphertext,
  *    Section "Results on Different Scales of Models").  The plaintext remainder (1-M).W is

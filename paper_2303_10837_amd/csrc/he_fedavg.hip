@@ -1267,6 +1267,9 @@ he_status launch_agg(he_ctx* ctx, bool has_acc, bool fin, const AggArgs& a, uint
   const uint32_t log_n4 = rg.logN - 2;
   const uint64_t n_vec = (n_ct * 2) << log_n4;
   if (((n_vec + 255) / 256) > 0x7FFFFFFFull) return fail(HE_ERR_INVALID_ARG, "too many ciphertexts for one launch");
+  uintptr_t align_bits = reinterpret_cast<uintptr_t>(acc_in) | reinterpret_cast<uintptr_t>(out);
+  for (uint32_t i = 0; i < a.K; ++i) align_bits |= reinterpret_cast<uintptr_t>(a.ct[i]);
+  if (align_bits % 16 != 0) return fail(HE_ERR_INVALID_ARG, "ciphertext buffers must be 16-byte aligned");
   KernelTimer timer_(ctx, KID_AGGREGATE, st);
   switch (rg.L) {
     case 2: launch_agg_l<2>(has_acc, fin, a, ctx->agg, log_n4, n_vec, acc_in, out, st); break;
@@ -1812,6 +1815,7 @@ static he_status encrypt_masked_impl(he_ctx* ctx, const he_pk* pk, const he_mask
   const uint64_t n_ct = he_n_ct(ctx, mask), n_plain = mk.P - mk.P_enc;
   if ((mk.P && !w_dev) || (n_ct && !ct_out_dev) || (n_plain && !plain_out_dev)) return fail(HE_ERR_INVALID_ARG, "null data pointer");
   if (n_ct >= (1ull << 32)) return fail(HE_ERR_INVALID_ARG, "too many ciphertexts");
+  if (reinterpret_cast<uintptr_t>(ct_out_dev) % 16 != 0) return fail(HE_ERR_INVALID_ARG, "ciphertext buffers must be 16-byte aligned");
   hipStream_t st = static_cast<hipStream_t>(stream);
   const RingDev& rg = ctx->ring;
   const uint64_t chunk = std::min<uint64_t>(kCtChunk, n_ct);
@@ -2042,6 +2046,7 @@ he_status he_debug_encrypt_plain(he_ctx* ctx, const he_pk* pk, uint64_t seed, ui
   if (n_ct == 0) return HE_OK;
   if (!pk || pk->ctx != ctx || !m_dev || !ct_out_dev) return fail(HE_ERR_INVALID_ARG, "null argument or key from another context");
   if (first_ct + n_ct > (1ull << 32)) return fail(HE_ERR_INVALID_ARG, "ciphertext index out of range");
+  if (reinterpret_cast<uintptr_t>(ct_out_dev) % 16 != 0) return fail(HE_ERR_INVALID_ARG, "ciphertext buffers must be 16-byte aligned");
   hipStream_t st = static_cast<hipStream_t>(stream);
   const RingDev& rg = ctx->ring;
   const size_t N = rg.N;

@@ -319,6 +319,10 @@ def test_mask_from_bytes_and_errors(he):
     for starts, lens in ([[10, 5], [3, 3]], [[0, 4], [5, 3]], [[0], [P + 1]], [[3], [0]]):
         with pytest.raises(he.HeError):
             he.he_mask_create(ctx, P, starts, lens)
+    # ciphertext buffers must be 16-byte aligned
+    buf = torch.empty(mask.n_ct * 2 * ctx.L * ctx.N + 1, dtype=torch.int32, device="cuda")
+    with pytest.raises(he.HeError):
+        he.he_encrypt_masked(ctx, keys, mask, SEED, 0, _dev(w), buf[1:])
     with pytest.raises(he.HeError):
         he.Context(16, 3)
     with pytest.raises(he.HeError):
