@@ -64,6 +64,18 @@ def measured_traffic(workload):
     return out
 
 
+def measured_valu_busy(workload):
+    """Vector-ALU busy percentage per kernel from the committed rocprofv3 VALUBusy summary, if any."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"valu_utilisation_{workload}.txt")
+    out = {}
+    if os.path.exists(path):
+        for line in open(path):
+            parts = line.split()
+            if len(parts) >= 3 and parts[0] == "valu_busy_pct":
+                out[parts[1]] = float(parts[2])
+    return out
+
+
 def cpu_baseline(w, ws_host, alpha, runs, budget_s=15.0, client_weighted=False):
     """Times the CPU oracle on a bounded sample of ciphertext indices of the same workload."""
     from oracle import fedavg as ofed, scheme as osch
@@ -304,6 +316,7 @@ def main():
     ntt_tops = ntt_coeff_per_s * ntt_ops_per_coeff / 1e12
     roofline_ntt = {"kernel": "k_ntt_batch_s", "bound": "alu", "achieved": ntt_tops, "peak": ALU_PEAK_TOPS, "unit": "TOP/s",
                     "frac": ntt_tops / ALU_PEAK_TOPS, "traffic": measured_traffic(w.name).get("k_ntt_batch"),
+                    "valu_busy_pct_profiled": measured_valu_busy(w.name).get("k_ntt_batch"),
                     "algorithmic_bytes_per_launch": batch * N * 8, "avg_launch_ms": ntt_ms / ntt_launches,
                     "launches": int(ntt_launches), "coeff_per_s": ntt_coeff_per_s, "ops_per_coeff": ntt_ops_per_coeff,
                     "hbm_GBps": ntt_coeff_per_s * 8 / 1e9, "hbm_frac": ntt_coeff_per_s * 8 / 1e9 / HBM_PEAK_GBS}
@@ -335,12 +348,14 @@ def main():
     traffic = measured_traffic(w.name)
     roofline = {"kernel": "k_encrypt", "bound": "alu", "achieved": enc_tops, "peak": ALU_PEAK_TOPS, "unit": "TOP/s",
                 "frac": enc_tops / ALU_PEAK_TOPS, "traffic": traffic.get("k_encrypt"),
+                "valu_busy_pct_profiled": measured_valu_busy(w.name).get("k_encrypt"),
                 "avg_launch_ms": enc_ms / max(enc_launches, 1), "launches": int(enc_launches),
                 "algorithmic_ops_per_launch": enc_ops / max(enc_launches, 1),
                 "algorithmic_bytes_per_launch": enc_bytes / max(enc_launches, 1),
                 "hbm_GBps": enc_bytes / (enc_ms * 1e-3) / 1e9 if enc_ms else 0.0}
     roofline_agg = {"kernel": "k_aggregate", "bound": "hbm", "achieved": agg_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": agg_gbs / HBM_PEAK_GBS, "traffic": traffic.get("k_aggregate"),
+                    "valu_busy_pct_profiled": measured_valu_busy(w.name).get("k_aggregate"),
                     "algorithmic_bytes_per_launch": agg_bytes / max(agg_launches, 1),
                     "avg_launch_ms": agg_ms / max(agg_launches, 1), "launches": int(agg_launches)}
 
