@@ -24,10 +24,10 @@ HBM_PEAK_GBS = 8000.0
 # for the integer butterfly instruction mix.
 ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # Operation counts of the integer butterflies as the kernels execute them (one 32-bit instruction each):
-OPS_BFLY_FWD = 12        # Shoup product (mul_hi, 2 mul_lo, sub) + its reduction (2) + modular add (3) + modular sub (3)
-OPS_BFLY_FWD_LAZY = 9    # outputs whose next use is a Shoup multiplicand stay in [0, 2q): add (1) + sub (2)
-OPS_BFLY_INV = 11        # modular add (3) + x - y + q (2) + Shoup product (4) + its reduction (2)
-OPS_POINTWISE = 6        # Shoup product + reduction
+OPS_BFLY_FWD = 11        # Shoup product (mul_hi, 2 x 64-bit multiply-add) + its reduction (2) + modular add (3) + modular sub (3)
+OPS_BFLY_FWD_LAZY = 8    # outputs whose next use is a Shoup multiplicand stay in [0, 2q): add (1) + sub (2)
+OPS_BFLY_INV = 10        # modular add (3) + x - y + q (2) + Shoup product (3) + its reduction (2)
+OPS_POINTWISE = 5        # Shoup product + reduction
 PASS_PLAN = {14: (4, 4, 3, 3), 13: (4, 3, 3, 3)}   # stages per LDS pass of the specialised transforms
 
 
@@ -36,7 +36,7 @@ def fwd_ops_per_coeff(log_n, lazy_last):
     the last pass is lazy when a key product follows (encrypt, decrypt).  Half a butterfly per coefficient and stage."""
     plan = PASS_PLAN.get(log_n)
     if plan is None:
-        return 0.5 * log_n * OPS_BFLY_FWD            # generic kernels: no lazy butterflies
+        return 0.5 * log_n * (OPS_BFLY_FWD + 1)      # generic kernels: four-instruction Shoup product, no lazy butterflies
     ops = 0.0
     for p, r in enumerate(plan):
         ops += (r - 1) * 0.5 * (OPS_BFLY_FWD + OPS_BFLY_FWD_LAZY) / 2

@@ -390,12 +390,12 @@ k_encrypt_s(RingDev rg, const uint2* __restrict__ pk, const int8_t* __restrict__
       uint32_t w[1][8];
       load_key8(kb, g << 3, k);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) w[0][i] = mul_shoup(v[0][i], k[i], q);
+      for (int i = 0; i < 8; ++i) w[0][i] = mul_shoup_mad<false>(v[0][i], k[i], q);
       bfly_stages<LOGN, S3, R3, true, 1>(w, g, twi, q);
       lds_store_group<LOGN, S3, R3>(A, g, w[0]);
       load_key8(ka, g << 3, k);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) w[0][i] = mul_shoup(v[0][i], k[i], q);
+      for (int i = 0; i < 8; ++i) w[0][i] = mul_shoup_mad<false>(v[0][i], k[i], q);
       bfly_stages<LOGN, S3, R3, true, 1>(w, g, twi, q);
       uint4* park = reinterpret_cast<uint4*>(out1 + (g << 3));
       park[0] = make_uint4(w[0][0], w[0][1], w[0][2], w[0][3]);  // ordinary stores: non-temporal ones measured 2 % slower
@@ -470,7 +470,7 @@ k_decrypt_s(RingDev rg, const uint2* __restrict__ sk, const uint32_t* __restrict
       uint2 k0[8];
       load_key8(key, g << 3, k0);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) v[0][i] = mul_shoup(v[0][i], k0[i], q);
+      for (int i = 0; i < 8; ++i) v[0][i] = mul_shoup_mad<false>(v[0][i], k0[i], q);
       bfly_stages<LOGN, S0, R, true, 1>(v, g, twi, q);
       lds_store_group<LOGN, S0, R>(A, g, v[0]);
     }

@@ -61,6 +61,7 @@ __device__ __forceinline__ void bfly_stages(uint32_t (&v)[NP][1 << R], int b, co
   using G = PassGeom<LOGN, S0, R>;
   constexpr int E = 1 << R;
   const int bb = (S0 == 0) ? 0 : (G::UNIFORM ? __builtin_amdgcn_readfirstlane(b) : b);
+  constexpr bool WS = (S0 == 0) || G::UNIFORM;  // twiddles are wave-uniform: scalar registers
   if (!INV) {
 #pragma unroll
     for (int k = 0; k < R; ++k) {
@@ -73,7 +74,7 @@ __device__ __forceinline__ void bfly_stages(uint32_t (&v)[NP][1 << R], int b, co
         const bool lazy = (k + 1 < R) ? ((i & (half >> 1)) != 0) : LAZY_LAST;
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
-          const uint32_t t = mul_shoup(v[p][i + half], w, q);
+          const uint32_t t = mul_shoup_mad<WS>(v[p][i + half], w, q);
           const uint32_t x = v[p][i];
           if (lazy) {
             v[p][i] = x + t;             // [0, 2q)
@@ -98,7 +99,7 @@ __device__ __forceinline__ void bfly_stages(uint32_t (&v)[NP][1 << R], int b, co
         for (int p = 0; p < NP; ++p) {
           const uint32_t x = v[p][i], y = v[p][i + half];
           v[p][i] = add_mod(x, y, q);
-          v[p][i + half] = mul_shoup(x - y + q, w, q);
+          v[p][i + half] = mul_shoup_mad<WS>(x - y + q, w, q);
         }
       }
     }
