@@ -23,7 +23,10 @@
  *  - All GPU work is enqueued on the given stream (a hipStream_t passed as void*; NULL is
  *    the default stream).  Calls are asynchronous with respect to the host except where a
  *    function says otherwise.  A context owns scratch memory: calls that share a context
- *    must be issued on one stream (or be externally ordered).
+ *    must be issued on one stream (or be externally ordered).  he_encrypt_masked and
+ *    he_decrypt_merge run the copy of the plaintext remainder on a stream of the context's
+ *    own (default priority), forked from and joined back into the given stream before the
+ *    call returns, so the ordering the caller sees is that of the given stream.
  *  - Ring: R = Z[X]/(X^N+1), N = 2^log2_n, n = N/2 slots per ciphertext (the paper's
  *    "packing batch size").  Modulus chain q_0 > ... > q_{L-1}, primes < 2^31, q = 1 mod 2N.
  *  - Ciphertext layout: uint32 [n_ct][2][level][N], coefficient domain, residues in [0,q_j),

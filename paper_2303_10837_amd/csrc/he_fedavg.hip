@@ -994,6 +994,10 @@ struct he_ctx {
   void* ws = nullptr;  // scratch, grown on demand
   size_t ws_bytes = 0;
   int max_lds = 0;
+  // The plaintext remainder (an HBM-bound copy) runs beside the ALU-bound transform kernels on a
+  // second stream of the context's own, forked from and joined back into the caller's stream.
+  hipStream_t side = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
 };
 
 struct he_pk {
@@ -1094,6 +1098,19 @@ uint32_t grid_for(uint64_t n, uint32_t block, uint32_t cap = 1u << 20) {
 he_status check_ctx(const he_ctx* ctx) {
   if (!ctx) return fail(HE_ERR_INVALID_ARG, "context is null");
   HIP_TRY(hipSetDevice(ctx->device));
+  return HE_OK;
+}
+
+// Work launched on ctx->side between fork and join runs concurrently with what the caller's
+// stream does in between, and is ordered before everything the caller enqueues after join.
+he_status side_fork(he_ctx* ctx, hipStream_t st) {
+  HIP_TRY(hipEventRecord(ctx->ev_fork, st));
+  HIP_TRY(hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0));
+  return HE_OK;
+}
+he_status side_join(he_ctx* ctx, hipStream_t st) {
+  HIP_TRY(hipEventRecord(ctx->ev_join, ctx->side));
+  HIP_TRY(hipStreamWaitEvent(st, ctx->ev_join, 0));
   return HE_OK;
 }
 
@@ -1378,6 +1395,12 @@ he_status he_ctx_create(const he_params* params, int device, he_ctx** out) {
   he_ctx* ctx = new (std::nothrow) he_ctx();
   if (!ctx) return fail(HE_ERR_NOMEM, "host allocation failed");
   ctx->device = device;
+  if (hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) != hipSuccess ||   // default priority
+      hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming) != hipSuccess) {
+    he_ctx_destroy(ctx);
+    return fail(HE_ERR_HIP, "could not create the context's side stream");
+  }
   const uint32_t logN = params->log2_n, N = 1u << logN, n = N / 2, L = params->n_limbs;
   if (params->primes) {
     ctx->primes.assign(params->primes, params->primes + L);
@@ -1510,6 +1533,9 @@ void he_ctx_destroy(he_ctx* ctx) {
     (void)hipEventDestroy(sp.stop);
   }
   for (hipEvent_t e : ctx->event_pool) (void)hipEventDestroy(e);
+  if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+  if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
+  if (ctx->side) (void)hipStreamDestroy(ctx->side);
   delete ctx;
 }
 
@@ -1825,17 +1851,16 @@ static he_status encrypt_masked_impl(he_ctx* ctx, const he_pk* pk, const he_mask
     if (s != HE_OK) return s;
   }
   const EncScratch sc = carve_enc_scratch(ctx->ws, chunk, N);
-  for (uint64_t c0 = 0; c0 < n_ct; c0 += chunk) {
-    const uint64_t cn = std::min<uint64_t>(chunk, n_ct - c0);
-    s = launch_encode(ctx, mk, w_dev, nullptr, c0, cn, sc.m, &sc, seed, client_id, st, pre_scale);
-    if (s != HE_OK) return s;
-    s = launch_encrypt(ctx, pk, cn, sc.m, sc, ct_out_dev + c0 * 2 * rg.L * N, st);
-    if (s != HE_OK) return s;
-  }
+  const bool beside = n_plain && n_ct;  // the copy of the remainder overlaps the transforms
+  hipStream_t pst = beside ? ctx->side : st;
   if (n_plain) {
+    if (beside) {
+      s = side_fork(ctx, st);
+      if (s != HE_OK) return s;
+    }
     {
-      KernelTimer timer_(ctx, KID_PLAIN_MOVE, st);
-      launch_plain_move<false>(mk, w_dev, plain_out_dev, st);
+      KernelTimer timer_(ctx, KID_PLAIN_MOVE, pst);
+      launch_plain_move<false>(mk, w_dev, plain_out_dev, pst);
       HIP_TRY(hipGetLastError());
     }
     if (pre_scale != 1.0) {  // weigh the compacted remainder in place: float32(alpha * x), product in float64
@@ -1843,10 +1868,18 @@ static he_status encrypt_masked_impl(he_ctx* ctx, const he_pk* pk, const he_mask
       pa.K = 1;
       pa.w[0] = plain_out_dev;
       pa.alpha[0] = pre_scale;
-      s = launch_plain(ctx, false, true, pa, n_plain, nullptr, nullptr, plain_out_dev, st);
+      s = launch_plain(ctx, false, true, pa, n_plain, nullptr, nullptr, plain_out_dev, pst);
       if (s != HE_OK) return s;
     }
   }
+  for (uint64_t c0 = 0; c0 < n_ct; c0 += chunk) {
+    const uint64_t cn = std::min<uint64_t>(chunk, n_ct - c0);
+    s = launch_encode(ctx, mk, w_dev, nullptr, c0, cn, sc.m, &sc, seed, client_id, st, pre_scale);
+    if (s != HE_OK) return s;
+    s = launch_encrypt(ctx, pk, cn, sc.m, sc, ct_out_dev + c0 * 2 * rg.L * N, st);
+    if (s != HE_OK) return s;
+  }
+  if (beside) return side_join(ctx, st);
   return HE_OK;
 }
 
@@ -2001,6 +2034,17 @@ static he_status decrypt_merge_impl(he_ctx* ctx, const he_sk* sk, const he_mask*
     if (s != HE_OK) return s;
   }
   uint32_t* d = static_cast<uint32_t*>(ctx->ws);
+  const bool beside = n_plain && n_ct;  // the scatter of the remainder writes other entries than the decoder does
+  hipStream_t pst = beside ? ctx->side : st;
+  if (n_plain) {
+    if (beside) {
+      s = side_fork(ctx, st);
+      if (s != HE_OK) return s;
+    }
+    KernelTimer timer_(ctx, KID_PLAIN_MOVE, pst);
+    launch_plain_move<true>(mk, plain_glob_dev, w_out_dev, pst);
+    HIP_TRY(hipGetLastError());
+  }
   for (uint64_t c0 = 0; c0 < n_ct; c0 += chunk) {
     const uint64_t cn = std::min<uint64_t>(chunk, n_ct - c0);
     s = launch_decrypt(ctx, sk, ct_glob_dev + c0 * 2 * level * N, cn, level, d, st);
@@ -2008,11 +2052,7 @@ static he_status decrypt_merge_impl(he_ctx* ctx, const he_sk* sk, const he_mask*
     s = launch_decode(ctx, level, mk, d, c0, cn, w_out_dev, nullptr, st);
     if (s != HE_OK) return s;
   }
-  if (n_plain) {
-    KernelTimer timer_(ctx, KID_PLAIN_MOVE, st);
-    launch_plain_move<true>(mk, plain_glob_dev, w_out_dev, st);
-    HIP_TRY(hipGetLastError());
-  }
+  if (beside) return side_join(ctx, st);
   return HE_OK;
 }
 
