@@ -5,12 +5,14 @@
 //   * every LDS access is `group base + immediate offset` (no per-element index arithmetic),
 //   * passes whose twiddles are the same for a whole wavefront fetch them with scalar loads,
 //   * the last forward pass, the pointwise key product and the first inverse pass of the
-//     encrypt / decrypt pipelines run back to back in registers (same group geometry), and
-//   * several polynomials that share twiddles (c0 and c1 of one ciphertext) go through the
-//     inverse passes together.
+//     encrypt / decrypt pipelines run back to back in registers (same group geometry),
+//   * passes 1..3 work on blocks that one wavefront owns, so only pass 0 needs workgroup
+//     barriers (see owned_group), and
+//   * the Shoup products take three instructions (mul_shoup_mad).
 //
 // Plan: N = 2^14 -> stages 4+4+3+3 (strides 1024, 64, 8, 1); N = 2^13 -> 4+3+3+3 (512, 64, 8, 1).
-// Every thread owns 16 coefficients per pass (one group of 16 or two groups of 8).
+// N/16 threads per workgroup: every thread owns 16 coefficients per pass (one group of 16 or
+// two groups of 8).
 #pragma once
 #include "he_device.hpp"
 
@@ -55,7 +57,7 @@ struct PassGeom {
 // multiplicand of a Shoup product (which accepts any 32-bit value): inside a pass that is
 // every element whose index has the next stage's pairing bit set (both outputs of a butterfly
 // share that bit); after the last stage of a pass only when the caller says so (LAZY_LAST: the
-// pass is followed by a pointwise key product).  Such a butterfly costs 9 operations, not 12.
+// pass is followed by a pointwise key product).  Such a butterfly costs 8 instructions, not 11.
 template <int LOGN, int S0, int R, bool INV, int NP, bool LAZY_LAST = false>
 __device__ __forceinline__ void bfly_stages(uint32_t (&v)[NP][1 << R], int b, const uint2* __restrict__ tw, uint32_t q) {
   using G = PassGeom<LOGN, S0, R>;
