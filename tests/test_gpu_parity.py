@@ -306,6 +306,66 @@ def test_client_weighted_variant(he, log2_n, limbs, K):
     assert np.abs(out[enc_idx] - ref[enc_idx]).max() < 16 * ofed.noise_sigma_client_weighted(p, K)
 
 
+@pytest.mark.parametrize("log2_n,limbs", [(13, 8), (14, 2), (12, 5), (14, 6)])
+def test_round_other_chain_lengths(he, log2_n, limbs):
+    """Chain lengths other than the benchmark's (shortest, longest, and the long ones on both specialised rings):
+    whole round, every ciphertext bit-exact, decoded values within 1e-6."""
+    ctx, keys, p, okeys = _setup(he, log2_n, limbs)
+    n = p.n_slots
+    P = n + n // 2 + 5
+    runs = [(2, n), (n + 10, n // 2 - 7)]
+    mask = he.he_mask_create(ctx, P, [r[0] for r in runs], [r[1] for r in runs])
+    enc_idx, plain_idx = ofed.mask_indices(P, runs)
+    rs = np.random.default_rng(10 + limbs)
+    K = 2
+    ws = [rs.normal(0, 0.05, P).astype(np.float32) for _ in range(K)]
+    alpha = np.array([0.625, 0.375])
+    cts, plains, ct_g, pl_g, out = _gpu_round(he, ctx, keys, mask, [_dev(w) for w in ws], alpha, SEED)
+    out = _np(out)
+    expect = np.zeros(P, dtype=np.float32)
+    expect[plain_idx] = ofed.plain_fedavg([w[plain_idx] for w in ws], alpha)
+    for c in range(mask.n_ct):
+        refs = []
+        for i in range(K):
+            z = ofed.pack_slots(p, ws[i], enc_idx, c)
+            m_gpu = _np(he.he_debug_encode(ctx, _dev(z.astype(np.float32)[None])))[0].astype(np.int64)
+            ref = osch.encrypt(p, okeys, m_gpu, SEED, i, c)
+            assert np.array_equal(_np(cts[i][c]).astype(np.int64), ref), (i, c)
+            refs.append(ref)
+        agg = osch.aggregate(p, refs, alpha)
+        assert np.array_equal(_np(ct_g[c]).astype(np.int64), agg)
+        sel = enc_idx[c * n:(c + 1) * n]
+        expect[sel] = ofed.decode_ct(p, okeys, agg)[:len(sel)].astype(np.float32)
+    assert np.array_equal(out[plain_idx], expect[plain_idx])
+    assert np.abs(out.astype(np.float64) - expect.astype(np.float64)).max() <= 1e-6
+
+
+@pytest.mark.parametrize("log2_n,limbs,seed", [(10, 3, 0), (13, 3, 1), (14, 4, 2)])
+def test_round_random_fragmented_masks(he, log2_n, limbs, seed):
+    """Masks made of hundreds of short random runs (many of length 1, many ciphertexts that straddle dozens of runs):
+    gather, compaction, scatter and merge against the oracle over the whole vector."""
+    ctx, keys, p, okeys = _setup(he, log2_n, limbs)
+    n = p.n_slots
+    rs = np.random.default_rng(100 + seed)
+    P = 3 * n + int(rs.integers(1, n))
+    cuts = np.sort(rs.choice(np.arange(1, P), size=min(P // 3, 1200), replace=False))
+    bounds = np.concatenate([[0], cuts, [P]])
+    runs = [(int(bounds[i]), int(bounds[i + 1] - bounds[i])) for i in range(int(rs.integers(0, 2)), len(bounds) - 1, 2)]
+    mask = he.he_mask_create(ctx, P, [r[0] for r in runs], [r[1] for r in runs])
+    enc_idx, plain_idx = ofed.mask_indices(P, runs)
+    K = 2
+    ws = [rs.normal(0, 0.05, P).astype(np.float32) for _ in range(K)]
+    alpha = np.array([0.3, 0.7])
+    cts, plains, ct_g, pl_g, out = _gpu_round(he, ctx, keys, mask, [_dev(w) for w in ws], alpha, SEED)
+    for i in range(K):
+        assert np.array_equal(_np(plains[i]), ws[i][plain_idx])
+    expect = ofed.secure_round(p, okeys, ws, alpha, runs, SEED)
+    out = _np(out)
+    assert np.array_equal(out[plain_idx], expect[plain_idx])
+    # the encoder's +-1 tolerance moves a decoded slot by about 2^-30 * sqrt(N): far inside 1e-6
+    assert np.abs(out.astype(np.float64) - expect.astype(np.float64)).max() <= 1e-6
+
+
 def test_mask_from_bytes_and_errors(he):
     ctx, keys, p, _ = _setup(he, 10, 3)
     P = 5000
