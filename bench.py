@@ -370,7 +370,12 @@ def main():
         "phases": {"encrypt_ms": phase_ms[0], "aggregate_ms": phase_ms[1], "decrypt_ms": phase_ms[2],
                    "encrypt_params_per_s": K * P_enc / (phase_ms[0] * 1e-3),
                    "aggregate_params_per_s": P_enc / (phase_ms[1] * 1e-3),
-                   "decrypt_params_per_s": P_enc / (phase_ms[2] * 1e-3)},
+                   "decrypt_params_per_s": P_enc / (phase_ms[2] * 1e-3),
+                   # the same rates as fractions of what HBM alone would allow: algorithmic bytes per encrypted
+                   # parameter are 4 + 16 L (encrypt), 16 K L + 16 L_out (aggregate), 16 L_out + 4 (decrypt)
+                   "encrypt_frac_of_hbm_roofline": K * P_enc / (phase_ms[0] * 1e-3) * (4 + 16 * L) / (HBM_PEAK_GBS * 1e9),
+                   "aggregate_frac_of_hbm_roofline": P_enc / (phase_ms[1] * 1e-3) * (16 * K * L + 16 * L_out) / (HBM_PEAK_GBS * 1e9),
+                   "decrypt_frac_of_hbm_roofline": P_enc / (phase_ms[2] * 1e-3) * (16 * L_out + 4) / (HBM_PEAK_GBS * 1e9)},
         "kernels_ms_per_step": {k: v[0] / args.steps for k, v in kern.items() if v[1]},
         "dominant_kernel": dominant,
         "roofline": roofline, "roofline_aggregate": roofline_agg, "roofline_ntt": roofline_ntt,
