@@ -359,6 +359,10 @@ def main():
                     "algorithmic_bytes_per_launch": agg_bytes / max(agg_launches, 1),
                     "avg_launch_ms": agg_ms / max(agg_launches, 1), "launches": int(agg_launches)}
 
+    n_pl = mask.n_plain
+    phase_bytes = [K * (4 * P_enc + 8 * n_pl + n_ct * 8 * L * N),                       # parameters read, remainder copied, ciphertexts written
+                   n_ct * 8 * N * (K * L + L_out) + n_pl * (4 * K + 4),               # K ciphertexts and remainders read, one of each written
+                   n_ct * 8 * L_out * N + 4 * P_enc + 8 * n_pl]                        # ciphertext read, parameters written, remainder copied
     res = {
         "metric": "encrypted params/sec (encrypt, aggregate, decrypt) + NTT/agg HBM GB/s % of peak",
         "value": K * P_enc / (ms_step * 1e-3), "unit": "params/s", "n_gpus": 1, "steps": args.steps,
@@ -371,11 +375,10 @@ def main():
                    "encrypt_params_per_s": K * P_enc / (phase_ms[0] * 1e-3),
                    "aggregate_params_per_s": P_enc / (phase_ms[1] * 1e-3),
                    "decrypt_params_per_s": P_enc / (phase_ms[2] * 1e-3),
-                   # the same rates as fractions of what HBM alone would allow: algorithmic bytes per encrypted
-                   # parameter are 4 + 16 L (encrypt), 16 K L + 16 L_out (aggregate), 16 L_out + 4 (decrypt)
-                   "encrypt_frac_of_hbm_roofline": K * P_enc / (phase_ms[0] * 1e-3) * (4 + 16 * L) / (HBM_PEAK_GBS * 1e9),
-                   "aggregate_frac_of_hbm_roofline": P_enc / (phase_ms[1] * 1e-3) * (16 * K * L + 16 * L_out) / (HBM_PEAK_GBS * 1e9),
-                   "decrypt_frac_of_hbm_roofline": P_enc / (phase_ms[2] * 1e-3) * (16 * L_out + 4) / (HBM_PEAK_GBS * 1e9)},
+                   # the same phases as fractions of what HBM alone would allow (algorithmic bytes of the phase / time / peak)
+                   "encrypt_frac_of_hbm_roofline": phase_bytes[0] / (phase_ms[0] * 1e-3) / (HBM_PEAK_GBS * 1e9),
+                   "aggregate_frac_of_hbm_roofline": phase_bytes[1] / (phase_ms[1] * 1e-3) / (HBM_PEAK_GBS * 1e9),
+                   "decrypt_frac_of_hbm_roofline": phase_bytes[2] / (phase_ms[2] * 1e-3) / (HBM_PEAK_GBS * 1e9)},
         "kernels_ms_per_step": {k: v[0] / args.steps for k, v in kern.items() if v[1]},
         "dominant_kernel": dominant,
         "roofline": roofline, "roofline_aggregate": roofline_agg, "roofline_ntt": roofline_ntt,
