@@ -222,6 +222,10 @@ def main():
                     help="also time the encryption-mask selection (top-p of a sensitivity map) on 25.6M / 110M / 1.3B entries")
     ap.add_argument("--k-sweep", action="store_true",
                     help="also time he_aggregate alone for K = 3 ... 200 clients (server cost against the number of clients)")
+    ap.add_argument("--stream-clients", action="store_true",
+                    help="fold each client's plaintext remainder into the server's accumulator right after its encryption "
+                         "(he_aggregate_begin/add/finalize) and keep only 4 distinct client vectors resident; chosen by "
+                         "itself when the clients' vectors exceed 64 GB")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (known HBM traffic, for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -244,19 +248,85 @@ def main():
     runs = [(int(s), int(l)) for s, l in zip(starts, lens)]
     mask = he.he_mask_create(ctx, w.n_params, starts, lens)
     alpha = si.client_alphas(w)
-    ws_host = [si.client_params_numpy(w, i) for i in range(K)]
-    ws = [torch.from_numpy(x).cuda() for x in ws_host]
+    # A workload whose client vectors do not fit next to all clients' ciphertexts (the 1.3 B-parameter one: 166 GB of
+    # inputs beside 133 GB of ciphertexts) keeps `n_distinct` vectors resident and hands client i vector i mod
+    # n_distinct (cost does not depend on the values); each client's plaintext remainder is folded into the float64
+    # accumulator right after its encryption (he_aggregate_add), and all K ciphertext sets stay resident and are
+    # streamed through he_aggregate once.
+    streamed = args.stream_clients or K * w.n_params * 4 > 64e9
+    n_distinct = min(K, 4) if streamed else K
+    if streamed:
+        ws = [si.client_params_torch(w, i, "cuda") for i in range(n_distinct)]
+        ws_host = [x.cpu().numpy() for x in ws]
+    else:
+        ws_host = [si.client_params_numpy(w, i) for i in range(K)]
+        ws = [torch.from_numpy(x).cuda() for x in ws_host]
+    ws = [ws[i % n_distinct] for i in range(K)]
+    ws_host = [ws_host[i % n_distinct] for i in range(K)]
     N, L, n_ct, P_enc = ctx.N, ctx.L, mask.n_ct, mask.P_enc
+    n_pl = mask.n_plain
     cts = [torch.empty((n_ct, 2, L, N), dtype=torch.int32, device="cuda") for _ in range(K)]
-    plains = [torch.empty((mask.n_plain,), dtype=torch.float32, device="cuda") for _ in range(K)]
+    plains = [] if streamed else [torch.empty((n_pl,), dtype=torch.float32, device="cuda") for _ in range(K)]
     L_out = L if client_weighted else L - 1
     ct_g = torch.empty((n_ct, 2, L_out, N), dtype=torch.int32, device="cuda")
-    pl_g = torch.empty((mask.n_plain,), dtype=torch.float32, device="cuda")
+    pl_g = torch.empty((n_pl,), dtype=torch.float32, device="cuda")
     out = torch.empty((w.n_params,), dtype=torch.float32, device="cuda")
+    # The server is its own party with its own copy of the public crypto context (it never holds a key).  In the
+    # streamed form it works on a second stream beside the clients: it folds the plaintext remainders of G clients at
+    # a time into its float64 accumulator while the next clients encrypt (HBM-bound beside ALU-bound work).
+    acc_none = acc_plain = ct_none = server = server_stream = None
+    G = 4
+    if streamed:
+        if client_weighted:
+            sys.exit("bench.py: --variant client_weighted is not combined with streamed clients")
+        server = he.Context(w.log2_n, n_limbs, w.scale_bits, w.cbd_eta)
+        server_stream = torch.cuda.Stream()
+        plains = [torch.empty((n_pl,), dtype=torch.float32, device="cuda") for _ in range(min(K, 2 * G))]
+        acc_none, acc_plain = he.he_aggregate_begin(server, 0, n_pl)
+        ct_none = torch.empty((0, 2, L_out, N), dtype=torch.int32, device="cuda")
+        torch.cuda.synchronize()
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
     phase_ms = np.zeros(3)
 
-    def step(record):
+    def step_streamed(record):
+        cur = torch.cuda.current_stream()
+        if record:
+            ev[0].record()
+        server_stream.wait_stream(cur)
+        if n_pl:
+            with torch.cuda.stream(server_stream):
+                he.he_aggregate_begin(server, 0, n_pl, acc_none, acc_plain)
+        folded = {}                                    # buffer half -> event: the server has read these remainders
+        for g0 in range(0, K, G):
+            grp = list(range(g0, min(g0 + G, K)))
+            half = (g0 // G) % 2
+            if half in folded:
+                cur.wait_event(folded[half])
+            slots = [half * G + (i - g0) for i in grp]
+            for i, sl in zip(grp, slots):
+                he.he_encrypt_masked(ctx, keys, mask, w.seed, i, ws[i], cts[i], plains[sl % len(plains)])
+            if n_pl:
+                sent = torch.cuda.Event()
+                sent.record(cur)
+                with torch.cuda.stream(server_stream):
+                    server_stream.wait_event(sent)
+                    he.he_aggregate_add(server, alpha[grp[0]:grp[-1] + 1], [None] * len(grp),
+                                        [plains[sl % len(plains)] for sl in slots], acc_none, acc_plain)
+                    folded[half] = torch.cuda.Event()
+                    folded[half].record(server_stream)
+        cur.wait_stream(server_stream)
+        if record:
+            ev[1].record()      # the encrypt phase of this form includes the server's folding of the remainders
+        he.he_aggregate(server, alpha, cts, [None] * K, ct_g, None)
+        if n_pl:
+            he.he_aggregate_finalize(server, acc_none, acc_plain, ct_none, pl_g)
+        if record:
+            ev[2].record()
+        he.he_decrypt_merge(ctx, keys, mask, ct_g, pl_g, out)
+        if record:
+            ev[3].record()
+
+    def step_resident(record):
         if record:
             ev[0].record()
         for i in range(K):
@@ -279,11 +349,23 @@ def main():
         if record:
             ev[3].record()
 
+    step = step_streamed if streamed else step_resident
+    timed_ctxs = [ctx] + ([server] if server is not None else [])
+
+    def timing_read():
+        tot = {}
+        for c in timed_ctxs:
+            for k, (ms, n) in he.he_debug_timing_read(c).items():
+                t = tot.get(k, (0.0, 0))
+                tot[k] = (t[0] + ms, t[1] + n)
+        return tot
+
     for _ in range(args.warmup):
         step(False)
     torch.cuda.synchronize()
-    he.he_debug_timing_enable(ctx, True)
-    he.he_debug_timing_read(ctx)
+    for c in timed_ctxs:
+        he.he_debug_timing_enable(c, True)
+    timing_read()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step(True)
@@ -291,8 +373,9 @@ def main():
         phase_ms += [ev[i].elapsed_time(ev[i + 1]) for i in range(3)]
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    kern = he.he_debug_timing_read(ctx)
-    he.he_debug_timing_enable(ctx, False)
+    kern = timing_read()
+    for c in timed_ctxs:
+        he.he_debug_timing_enable(c, False)
     ms_step = dt * 1e3 / args.steps
     phase_ms /= args.steps
 
@@ -363,12 +446,15 @@ def main():
     phase_bytes = [K * (4 * P_enc + 8 * n_pl + n_ct * 8 * L * N),                       # parameters read, remainder copied, ciphertexts written
                    n_ct * 8 * N * (K * L + L_out) + n_pl * (4 * K + 4),               # K ciphertexts and remainders read, one of each written
                    n_ct * 8 * L_out * N + 4 * P_enc + 8 * n_pl]                        # ciphertext read, parameters written, remainder copied
+    if streamed:   # the K reads of the remainders happen while the clients encrypt; only the final write is in the server phase
+        phase_bytes[0] += n_pl * 4 * K
+        phase_bytes[1] -= n_pl * 4 * K
     res = {
         "metric": "encrypted params/sec (encrypt, aggregate, decrypt) + NTT/agg HBM GB/s % of peak",
         "value": K * P_enc / (ms_step * 1e-3), "unit": "params/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "u32", "data": "synthetic",
-        "config": {"workload": w.name, "variant": args.variant, "clients": K, "params_per_client": w.n_params, "encrypted_params": P_enc,
+        "config": {"workload": w.name, "variant": args.variant, "streamed_clients": streamed, "distinct_client_vectors": n_distinct, "clients": K, "params_per_client": w.n_params, "encrypted_params": P_enc,
                    "n_ct_per_client": n_ct, "ring_degree": N, "limbs": L, "scale_bits": w.scale_bits,
                    "value_definition": "clients * encrypted_params / step time; step = all clients encrypt + aggregate + decrypt"},
         "phases": {"encrypt_ms": phase_ms[0], "aggregate_ms": phase_ms[1], "decrypt_ms": phase_ms[2],
