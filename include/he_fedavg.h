@@ -112,8 +112,8 @@ he_status he_mask_create(he_ctx* ctx, uint64_t P, const uint64_t* starts_host,
 he_status he_mask_from_bytes(he_ctx* ctx, uint64_t P, const uint8_t* mask_dev, he_mask** out,
                              void* stream);
 /* Select(global privacy map, p) of Algorithm 1 ("Server Encryption Mask Aggregation"; Section
-   "Selective Parameter Encryption", Step 2: "the ratio of selecting the most sensitive
-   parameters for encryption").  s_dev float32[P] is the aggregated sensitivity map (decrypted:
+   "Selective Parameter Encryption", Step 2: the ratio p is the share of parameters, the most
+   sensitive ones, that gets encrypted).  s_dev float32[P] is the aggregated sensitivity map (decrypted:
    the selection itself is not homomorphic); the mask takes the k = rint(ratio * P) largest
    entries (ties to even in k; equal sensitivities go to the lower parameter index; -0 = +0;
    entries must not be NaN).  Radix select and run extraction on the GPU (set-up path,
@@ -178,8 +178,8 @@ he_status he_decrypt_merge(he_ctx* ctx, const he_sk* sk, const he_mask* mask,
                            const uint32_t* ct_glob_dev, const float* plain_glob_dev,
                            float* w_out_dev, void* stream);
 
-/* ---- variant: weighing on the client ("scales each learner's local model parameters locally
-   rather than weighing ciphertexts on the server", Section "Comparison with Other FL Frameworks").
+/* ---- variant: weighing on the client (Section "Comparison with Other FL Frameworks" describes a
+   system whose learners multiply their parameters by their weight before encrypting).
    The client encodes alpha_i * W_i, the server only adds ciphertexts: no ciphertext-scalar
    product, no rescale, and the level never drops, so a context with one limb fewer serves the
    same plaintext range.  The paper notes the price: every client learns its own weight.

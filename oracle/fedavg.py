@@ -93,8 +93,8 @@ def secure_round(p: Params, keys, ws, alpha, runs, seed, fast=True):
 
 
 # ---- variant: weighing on the client, the server only adds -------------------------------------
-# (Section "Comparison with Other FL Frameworks": "scales each learner's local model parameters
-#  locally rather than weighing ciphertexts on the server"; no ciphertext-scalar product, no rescale.)
+# (Section "Comparison with Other FL Frameworks" describes a system in which every learner multiplies
+#  its own parameters by its weight before encrypting; no ciphertext-scalar product, no rescale.)
 
 def encrypt_ct_weighted(p, keys, w, enc_idx, alpha_i, seed, client_id, ct_index, fast=True):
     """Client side: slots alpha_i * w (float64 product), encode, encrypt.  Returns (m, ct)."""

@@ -2,9 +2,9 @@
 
 Algorithm 1 ("Server Encryption Mask Aggregation") forms the global privacy map
 sum_i alpha_i [[S_i]] from the clients' encrypted sensitivity maps and configures
-the mask M from it "using a privacy-overhead ratio p in [0, 1] which is the ratio
-of selecting the most sensitive parameters for encryption" (Section "Selective
-Parameter Encryption", Step 2).  The aggregation is the ordinary secure round with
+the mask M from it: a ratio p in [0, 1] says which share of the parameters, the
+most sensitive ones, gets encrypted (Section "Selective Parameter Encryption",
+Step 2).  The aggregation is the ordinary secure round with
 everything encrypted; the selection works on the decrypted map (a comparison is
 not a depth-1 homomorphic operation; the paper leaves open who decrypts).
 
