@@ -154,7 +154,8 @@ k_encode(RingDev rg, MaskDev mk, const float* __restrict__ w, const float* __res
 // workgroup; every Philox block is drawn exactly once.
 template <int NT>
 __device__ __forceinline__ void sample_ct(const RngKey& rk, uint32_t N, uint32_t eta, int8_t* __restrict__ u_out,
-                                          int8_t* __restrict__ e0_out, int8_t* __restrict__ e1_out) {
+                                          int8_t* __restrict__ e0_out, int8_t* __restrict__ e1_out, uint32_t it0 = 0,
+                                          uint32_t it1 = 0xFFFFFFFFu) {
   const uint32_t mask = eta == 0 ? 0u : cbd_mask(eta);
   uint32_t* u32 = reinterpret_cast<uint32_t*>(u_out);
   uint32_t* e0w = reinterpret_cast<uint32_t*>(e0_out);
@@ -162,7 +163,8 @@ __device__ __forceinline__ void sample_ct(const RngKey& rk, uint32_t N, uint32_t
   auto pack4 = [](int a, int b, int c, int d) {
     return (uint32_t)(uint8_t)a | ((uint32_t)(uint8_t)b << 8) | ((uint32_t)(uint8_t)c << 16) | ((uint32_t)(uint8_t)d << 24);
   };
-  for (uint32_t b = threadIdx.x; b < N / 4; b += NT) {  // 4 coefficients per iteration and stream
+  // 4 coefficients per iteration and stream; iterations [it0, it1) of the N / (4 NT) a thread owns
+  for (uint32_t it = it0, b = threadIdx.x + it0 * NT; it < it1 && b < N / 4; ++it, b += NT) {
     const uint4 r = rng_block(rk, b, kTagU);
     u32[b] = pack4(ternary_from_word(r.x), ternary_from_word(r.y), ternary_from_word(r.z), ternary_from_word(r.w));
     const uint4 a0 = rng_block(rk, 2 * b, kTagE0), a1 = rng_block(rk, 2 * b + 1, kTagE0);
@@ -230,6 +232,15 @@ k_encode_r(RingDev rg, MaskDev mk, const float* __restrict__ w, const float* __r
       }
     }
   }
+  // The ciphertext's randomness (u, e0, e1) is drawn in this kernel too, in slices placed where the encoder waits:
+  // behind the gather loads and in front of every barrier.  The sampler is pure integer arithmetic, the transform
+  // waits on LDS, twiddle loads and barriers, and the slices of one wavefront fill the waits of the others.
+  static_assert(N / 4 / P::NT == 8, "eight sampler iterations per thread");
+  const RngKey rk{key, (uint32_t)c, client};
+  auto sample = [&](uint32_t it0, uint32_t it1) {
+    if (u_out) sample_ct<P::NT>(rk, N, rg.eta, u_out + c_local * N, e0_out + c_local * N, e1_out + c_local * N, it0, it1);
+  };
+  sample(0, 3);
 #pragma unroll
   for (int u = 0; u < U; ++u) ((code[u] & 1) ? im : re)[fswz<LOGh>((int)(code[u] >> 1))] = (double)z[u] * pre_scale;
   __syncthreads();
@@ -237,12 +248,16 @@ k_encode_r(RingDev rg, MaskDev mk, const float* __restrict__ w, const float* __r
   auto ldl = [=](int a, double& r, double& i) { r = re[fswz<LOGh>(a)]; i = im[fswz<LOGh>(a)]; };
   auto stl = [=](int a, double r, double i) { re[fswz<LOGh>(a)] = r; im[fswz<LOGh>(a)] = i; };
   fft_pass<LOGh, 3, true, false, 1>(e_tab, ldl, stl);
+  sample(3, 4);
   __syncthreads();
   fft_pass<LOGh, 2, true, false, 1>(e_tab, ldl, stl);
+  sample(4, 5);
   __syncthreads();
   fft_pass<LOGh, 1, true, false, 1>(e_tab, ldl, stl);
+  sample(5, 6);
   __syncthreads();
   fft_pass<LOGh, 0, true, false, 1>(e_tab, ldl, stl);
+  sample(6, 7);
   __syncthreads();
   static_assert(P::kPasses == 4, "plans of the half-length transforms have four passes");
   const double scale = ldexp(1.0, (int)rg.scale_bits - LOGh - 2);  // Delta / n, and the 1/2 of the split step
@@ -266,12 +281,7 @@ k_encode_r(RingDev rg, MaskDev mk, const float* __restrict__ w, const float* __r
     out[k + h] = __double2int_rn((a1r * t1.x + a1i * t1.y) * scale);
     out[k + h + n] = __double2int_rn((a1i * t1.x - a1r * t1.y) * scale);
   }
-  // The ciphertext's randomness is drawn here too: the encoder waits on memory most of the time,
-  // the sampler is pure integer arithmetic, and the two overlap across the resident wavefronts.
-  if (u_out) {
-    const RngKey rk{key, (uint32_t)c, client};
-    sample_ct<P::NT>(rk, N, rg.eta, u_out + c_local * N, e0_out + c_local * N, e1_out + c_local * N);
-  }
+  sample(7, 8);
 }
 
 // ---- a4: public-key encryption of one (ciphertext, limb) --------------------------------
