@@ -69,6 +69,52 @@ def test_context_and_transform(he, log2_n, limbs):
         assert np.array_equal(_np(d).astype(np.int64), polys)
 
 
+def _boundary_values(rs, q, shape):
+    """Residues at the edges of the lazy ranges the kernels keep: 0, 1, q-1, q-2, (q-1)/2, (q+1)/2, mixed at random
+    with a few ordinary values."""
+    edge = np.array([0, 1, q - 1, q - 2, (q - 1) // 2, (q + 1) // 2, 2, q - 3], dtype=np.int64)
+    v = edge[rs.integers(0, len(edge), shape)]
+    ordinary = rs.random(shape) < 0.1
+    v[ordinary] = rs.integers(0, q, int(ordinary.sum()))
+    return v
+
+
+@pytest.mark.parametrize("log2_n,limbs", [(10, 3), (13, 3), (14, 4)])
+def test_transform_and_decrypt_on_boundary_values(he, log2_n, limbs):
+    """Inputs made of the extreme residues (every butterfly sees sums and differences at the edges of [0, q) and
+    [0, 2q)): the transforms, and decryption of ciphertexts made of such residues, stay bit-exact."""
+    ctx, keys, p, okeys = _setup(he, log2_n, limbs)
+    rs = np.random.default_rng(100 + log2_n)
+    for j, q in enumerate(p.primes):
+        polys = _boundary_values(rs, q, (12, p.N))
+        d = _dev(polys, torch.int32)
+        he.he_debug_ntt(ctx, False, j, d)
+        fwd = _np(d).astype(np.int64)
+        for b in range(polys.shape[0]):
+            assert np.array_equal(fwd[b], oring.ntt(polys[b], q, p.psi(j))), (log2_n, j, b)
+        he.he_debug_ntt(ctx, True, j, d)
+        assert np.array_equal(_np(d).astype(np.int64), polys)
+        # inverse first, from boundary values in the evaluation domain
+        d = _dev(polys, torch.int32)
+        he.he_debug_ntt(ctx, True, j, d)
+        inv = _np(d).astype(np.int64)
+        for b in range(0, polys.shape[0], 4):
+            assert np.array_equal(inv[b], oring.intt(polys[b], q, p.psi(j))), (log2_n, j, b)
+    cts = np.stack([_boundary_values(rs, q, (3, 2, p.N)) for q in p.primes], axis=2)
+    for lvl in (limbs - 1, limbs):
+        got = _np(he.he_debug_decrypt_residues(ctx, keys, _dev(cts[:, :, :lvl], torch.int32), lvl)).astype(np.int64)
+        for c in range(cts.shape[0]):
+            assert np.array_equal(got[c], osch.decrypt_residues(p, okeys, cts[c][:, :lvl], lvl)), (log2_n, lvl, c)
+    # aggregation of such ciphertexts with weights at the ends of their range
+    K = 5
+    alpha = np.array([1e-6, 0.5, 0.25, 0.2, 1.0 - 0.95 - 1e-6])
+    ins = [np.stack([_boundary_values(rs, q, (2, 2, p.N)) for q in p.primes], axis=2) for _ in range(K)]
+    out, _ = he.he_aggregate(ctx, alpha, [_dev(x, torch.int32) for x in ins], [None] * K)
+    out = _np(out).astype(np.int64)
+    for c in range(2):
+        assert np.array_equal(out[c], osch.aggregate(p, [x[c] for x in ins], alpha)), (log2_n, c)
+
+
 @pytest.mark.parametrize("log2_n,limbs", [(4, 3), (10, 3), (13, 3), (14, 4)])
 def test_keygen(he, log2_n, limbs):
     ctx, keys, p, okeys = _setup(he, log2_n, limbs)
