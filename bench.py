@@ -397,6 +397,14 @@ def main():
         he.he_debug_timing_enable(c, False)
     ms_step = dt * 1e3 / args.steps
     phase_ms /= args.steps
+    # The same steps once more without the per-kernel event pairs and without reading the phases back after every
+    # step: what the instrumentation of the timed region above costs (reported beside `value`, never as `value`).
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(False)
+    torch.cuda.synchronize()
+    ms_step_plain = (time.perf_counter() - t0) * 1e3 / args.steps
 
     # standalone transform throughput (he_debug_ntt, in place): forward then inverse over a batch
     batch = 4096
@@ -484,6 +492,8 @@ def main():
                    "encrypt_frac_of_hbm_roofline": phase_bytes[0] / (phase_ms[0] * 1e-3) / (HBM_PEAK_GBS * 1e9),
                    "aggregate_frac_of_hbm_roofline": phase_bytes[1] / (phase_ms[1] * 1e-3) / (HBM_PEAK_GBS * 1e9),
                    "decrypt_frac_of_hbm_roofline": phase_bytes[2] / (phase_ms[2] * 1e-3) / (HBM_PEAK_GBS * 1e9)},
+        "uninstrumented": {"ms_per_step": ms_step_plain, "value": K * P_enc / (ms_step_plain * 1e-3),
+                           "note": "same steps without the per-kernel event pairs and per-step read-back of the timed region"},
         "kernels_ms_per_step": {k: v[0] / args.steps for k, v in kern.items() if v[1]},
         "dominant_kernel": dominant,
         "roofline": roofline, "roofline_aggregate": roofline_agg, "roofline_ntt": roofline_ntt,

@@ -27,6 +27,10 @@
  *    he_decrypt_merge run the copy of the plaintext remainder on a stream of the context's
  *    own (default priority), forked from and joined back into the given stream before the
  *    call returns, so the ordering the caller sees is that of the given stream.
+ *    The calls of the round (he_encrypt_masked, he_aggregate*, he_decrypt_merge*) can be recorded
+ *    into a HIP graph by stream capture once a first eager call with the same sizes has grown the
+ *    context's scratch: after that they allocate nothing, synchronise nothing and clear memory with
+ *    kernels.  The set-up calls (contexts, keys, masks) cannot.
  *  - Ring: R = Z[X]/(X^N+1), N = 2^log2_n, n = N/2 slots per ciphertext (the paper's
  *    "packing batch size").  Modulus chain q_0 > ... > q_{L-1}, primes < 2^31, q = 1 mod 2N.
  *  - Ciphertext layout: uint32 [n_ct][2][level][N], coefficient domain, residues in [0,q_j),
