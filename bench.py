@@ -386,19 +386,22 @@ def main():
         he.he_debug_timing_enable(c, True)
     timing_read()
     t0 = time.perf_counter()
+    step_events = []
     for _ in range(args.steps):
+        ev[:] = [torch.cuda.Event(enable_timing=True) for _ in range(4)]   # own events per step, read after the region
+        step_events.append(list(ev))
         step(True)
-        ev[3].synchronize()   # phases of a step are read back while nothing else is queued
-        phase_ms += [ev[i].elapsed_time(ev[i + 1]) for i in range(3)]
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    for e4 in step_events:
+        phase_ms += [e4[i].elapsed_time(e4[i + 1]) for i in range(3)]
     kern = timing_read()
     for c in timed_ctxs:
         he.he_debug_timing_enable(c, False)
     ms_step = dt * 1e3 / args.steps
     phase_ms /= args.steps
-    # The same steps once more without the per-kernel event pairs and without reading the phases back after every
-    # step: what the instrumentation of the timed region above costs (reported beside `value`, never as `value`).
+    # The same steps once more without the per-kernel event pairs and the phase events: what the instrumentation of
+    # the timed region above costs (reported beside `value`, never as `value`).
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -493,7 +496,7 @@ def main():
                    "aggregate_frac_of_hbm_roofline": phase_bytes[1] / (phase_ms[1] * 1e-3) / (HBM_PEAK_GBS * 1e9),
                    "decrypt_frac_of_hbm_roofline": phase_bytes[2] / (phase_ms[2] * 1e-3) / (HBM_PEAK_GBS * 1e9)},
         "uninstrumented": {"ms_per_step": ms_step_plain, "value": K * P_enc / (ms_step_plain * 1e-3),
-                           "note": "same steps without the per-kernel event pairs and per-step read-back of the timed region"},
+                           "note": "same steps without the per-kernel event pairs and phase events of the timed region"},
         "kernels_ms_per_step": {k: v[0] / args.steps for k, v in kern.items() if v[1]},
         "dominant_kernel": dominant,
         "roofline": roofline, "roofline_aggregate": roofline_agg, "roofline_ntt": roofline_ntt,
