@@ -515,7 +515,6 @@ k_ntt_batch_s(RingDev rg, int limb, uint32_t* __restrict__ polys) {
   const uint32_t q = rg.q[j];
   uint32_t* x = polys + (size_t)blockIdx.x * N;
   constexpr int S3 = P::S[3], R3 = P::R[3];
-  using G3 = PassGeom<LOGN, S3, R3>;
   if (!INV) {
     const uint2* twf = rg.tw_fwd + (size_t)j * N;
     fwd_head<LOGN>(A, twf, q, [=](int a) { return x[a]; });
@@ -970,6 +969,16 @@ he_status fail(he_status code, const std::string& msg) {
   return code;
 }
 
+// No exception leaves the library: host containers may throw std::bad_alloc, which every entry point turns into
+// HE_ERR_NOMEM (the message fits the string's inline buffer, so setting it allocates nothing).
+he_status on_exception() {
+  try {
+    g_last_error.assign("out of memory");
+  } catch (...) {
+  }
+  return HE_ERR_NOMEM;
+}
+
 #define HIP_TRY(expr)                                                                         \
   do {                                                                                        \
     hipError_t e_ = (expr);                                                                   \
@@ -1396,7 +1405,7 @@ extern "C" {
 
 const char* he_last_error(void) { return g_last_error.c_str(); }
 
-he_status he_ctx_create(const he_params* params, int device, he_ctx** out) {
+he_status he_ctx_create(const he_params* params, int device, he_ctx** out) try {
   if (!params || !out) return fail(HE_ERR_INVALID_ARG, "params/out is null");
   *out = nullptr;
   if (params->log2_n < 3 || params->log2_n > 14) return fail(HE_ERR_INVALID_ARG, "log2_n must be in 3..14");
@@ -1420,12 +1429,12 @@ he_status he_ctx_create(const he_params* params, int device, he_ctx** out) {
       const uint32_t q = ctx->primes[j];
       if (q <= (1u << 30) || q >= (1u << 31) || (q - 1) % (2 * N) != 0 || !he_host::is_prime_u32(q) ||
           (j > 0 && q >= ctx->primes[j - 1])) {
-        delete ctx;
+        he_ctx_destroy(ctx);
         return fail(HE_ERR_INVALID_ARG, "primes must be descending primes in (2^30, 2^31) with q = 1 mod 2N");
       }
     }
   } else if (!he_host::find_primes(logN, L, &ctx->primes) || ctx->primes.back() <= (1u << 30)) {
-    delete ctx;
+    he_ctx_destroy(ctx);
     return fail(HE_ERR_INVALID_ARG, "not enough primes below 2^31 for this ring");
   }
   RingDev& rg = ctx->ring;
@@ -1532,6 +1541,8 @@ he_status he_ctx_create(const he_params* params, int device, he_ctx** out) {
   }
   *out = ctx;
   return HE_OK;
+} catch (...) {
+  return on_exception();
 }
 
 void he_ctx_destroy(he_ctx* ctx) {
@@ -1551,10 +1562,12 @@ void he_ctx_destroy(he_ctx* ctx) {
   delete ctx;
 }
 
-he_status he_ctx_primes(const he_ctx* ctx, uint32_t* primes_host) {
+he_status he_ctx_primes(const he_ctx* ctx, uint32_t* primes_host) try {
   if (!ctx || !primes_host) return fail(HE_ERR_INVALID_ARG, "null argument");
   std::copy(ctx->primes.begin(), ctx->primes.end(), primes_host);
   return HE_OK;
+} catch (...) {
+  return on_exception();
 }
 
 uint32_t he_ctx_ring_degree(const he_ctx* ctx) { return ctx ? ctx->ring.N : 0; }
@@ -1563,7 +1576,7 @@ uint64_t he_ct_bytes(const he_ctx* ctx, uint32_t level) { return ctx ? 2ull * le
 
 // ---- keys ------------------------------------------------------------------------------
 
-he_status he_keygen(he_ctx* ctx, uint64_t seed, he_pk** pk_out, he_sk** sk_out, void* stream) {
+he_status he_keygen(he_ctx* ctx, uint64_t seed, he_pk** pk_out, he_sk** sk_out, void* stream) try {
   he_status s = check_ctx(ctx);
   if (s != HE_OK) return s;
   if (!pk_out || !sk_out) return fail(HE_ERR_INVALID_ARG, "pk/sk out pointer is null");
@@ -1613,6 +1626,8 @@ he_status he_keygen(he_ctx* ctx, uint64_t seed, he_pk** pk_out, he_sk** sk_out, 
   *pk_out = pk;
   *sk_out = sk;
   return HE_OK;
+} catch (...) {
+  return on_exception();
 }
 
 void he_pk_destroy(he_pk* pk) {
@@ -1632,7 +1647,7 @@ void he_sk_destroy(he_sk* sk) {
 // ---- mask ------------------------------------------------------------------------------
 
 he_status he_mask_create(he_ctx* ctx, uint64_t P, const uint64_t* starts, const uint64_t* lens, uint64_t n_runs,
-                         he_mask** out) {
+                         he_mask** out) try {
   he_status s = check_ctx(ctx);
   if (s != HE_OK) return s;
   if (!out || (n_runs && (!starts || !lens))) return fail(HE_ERR_INVALID_ARG, "null argument");
@@ -1689,11 +1704,13 @@ he_status he_mask_create(he_ctx* ctx, uint64_t P, const uint64_t* starts, const 
   mk->lens.assign(lens, lens + n_runs);
   *out = mk;
   return HE_OK;
+} catch (...) {
+  return on_exception();
 }
 
 // Run list of a device byte mask (non-zero = selected), extracted on the GPU: per-chunk counts of
 // run starts and ends, an exclusive scan, an emit pass; only the runs themselves travel to the host.
-static he_status mask_from_device_bytes(he_ctx* ctx, uint64_t P, const uint8_t* mask_dev, he_mask** out, hipStream_t st) {
+static he_status mask_from_device_bytes(he_ctx* ctx, uint64_t P, const uint8_t* mask_dev, he_mask** out, hipStream_t st) try {
   using namespace he_sel;
   if (P == 0) return he_mask_create(ctx, 0, nullptr, nullptr, 0, out);
   const uint64_t n_chunks = (P + kChunk - 1) / kChunk;
@@ -1747,16 +1764,20 @@ static he_status mask_from_device_bytes(he_ctx* ctx, uint64_t P, const uint8_t* 
   cleanup();
 #undef MK_TRY
   return he_mask_create(ctx, P, starts.data(), lens.data(), R, out);
+} catch (...) {
+  return on_exception();
 }
 
-he_status he_mask_from_bytes(he_ctx* ctx, uint64_t P, const uint8_t* mask_dev, he_mask** out, void* stream) {
+he_status he_mask_from_bytes(he_ctx* ctx, uint64_t P, const uint8_t* mask_dev, he_mask** out, void* stream) try {
   he_status s = check_ctx(ctx);
   if (s != HE_OK) return s;
   if (!out || (P && !mask_dev)) return fail(HE_ERR_INVALID_ARG, "null argument");
   return mask_from_device_bytes(ctx, P, mask_dev, out, static_cast<hipStream_t>(stream));
+} catch (...) {
+  return on_exception();
 }
 
-he_status he_mask_select_top(he_ctx* ctx, uint64_t P, const float* s_dev, double ratio, he_mask** out, void* stream) {
+he_status he_mask_select_top(he_ctx* ctx, uint64_t P, const float* s_dev, double ratio, he_mask** out, void* stream) try {
   using namespace he_sel;
   he_status s = check_ctx(ctx);
   if (s != HE_OK) return s;
@@ -1816,6 +1837,8 @@ he_status he_mask_select_top(he_ctx* ctx, uint64_t P, const float* s_dev, double
   s = mask_from_device_bytes(ctx, P, mask_dev, out, st);  // synchronises the stream before it returns
   (void)hipFree(tmp);
   return s;
+} catch (...) {
+  return on_exception();
 }
 
 void he_mask_destroy(he_mask* mask) {
@@ -1826,11 +1849,13 @@ void he_mask_destroy(he_mask* mask) {
 
 uint64_t he_mask_n_runs(const he_mask* mask) { return mask ? mask->starts.size() : 0; }
 
-he_status he_mask_runs(const he_mask* mask, uint64_t* starts_host, uint64_t* lens_host) {
+he_status he_mask_runs(const he_mask* mask, uint64_t* starts_host, uint64_t* lens_host) try {
   if (!mask || ((!starts_host || !lens_host) && !mask->starts.empty())) return fail(HE_ERR_INVALID_ARG, "null argument");
   std::copy(mask->starts.begin(), mask->starts.end(), starts_host);
   std::copy(mask->lens.begin(), mask->lens.end(), lens_host);
   return HE_OK;
+} catch (...) {
+  return on_exception();
 }
 
 uint64_t he_mask_n_params(const he_mask* mask) { return mask ? mask->dev.P : 0; }
@@ -1845,7 +1870,7 @@ uint64_t he_n_ct(const he_ctx* ctx, const he_mask* mask) {
 
 static he_status encrypt_masked_impl(he_ctx* ctx, const he_pk* pk, const he_mask* mask, uint64_t seed, uint32_t client_id,
                                      double pre_scale, const float* w_dev, uint32_t* ct_out_dev, float* plain_out_dev,
-                                     void* stream) {
+                                     void* stream) try {
   he_status s = check_ctx(ctx);
   if (s != HE_OK) return s;
   if (!pk || !mask || pk->ctx != ctx || mask->ctx != ctx) return fail(HE_ERR_INVALID_ARG, "key/mask missing or from another context");
@@ -1893,25 +1918,31 @@ static he_status encrypt_masked_impl(he_ctx* ctx, const he_pk* pk, const he_mask
   }
   if (beside) return side_join(ctx, st);
   return HE_OK;
+} catch (...) {
+  return on_exception();
 }
 
 he_status he_encrypt_masked(he_ctx* ctx, const he_pk* pk, const he_mask* mask, uint64_t seed, uint32_t client_id,
-                            const float* w_dev, uint32_t* ct_out_dev, float* plain_out_dev, void* stream) {
+                            const float* w_dev, uint32_t* ct_out_dev, float* plain_out_dev, void* stream) try {
   return encrypt_masked_impl(ctx, pk, mask, seed, client_id, 1.0, w_dev, ct_out_dev, plain_out_dev, stream);
+} catch (...) {
+  return on_exception();
 }
 
 he_status he_encrypt_masked_weighted(he_ctx* ctx, const he_pk* pk, const he_mask* mask, uint64_t seed, uint32_t client_id,
                                      double alpha, const float* w_dev, uint32_t* ct_out_dev, float* plain_out_dev,
-                                     void* stream) {
+                                     void* stream) try {
   if (!(alpha > 0.0) || !(alpha <= 1.0)) return fail(HE_ERR_INVALID_ARG, "aggregation weight must be in (0, 1]");
   return encrypt_masked_impl(ctx, pk, mask, seed, client_id, alpha, w_dev, ct_out_dev, plain_out_dev, stream);
+} catch (...) {
+  return on_exception();
 }
 
 // ---- server: aggregate -----------------------------------------------------------------
 
 he_status he_aggregate(he_ctx* ctx, uint32_t K, const double* alpha_host, const uint32_t* const* ct_in_dev,
                        const float* const* plain_in_dev, uint64_t n_ct, uint64_t n_plain, uint32_t* ct_out_dev,
-                       float* plain_out_dev, void* stream) {
+                       float* plain_out_dev, void* stream) try {
   he_status s = check_ctx(ctx);
   if (s != HE_OK) return s;
   if (K == 0 || K > HE_MAX_CLIENTS_PER_CALL) return fail(HE_ERR_INVALID_ARG, "K must be in 1..HE_MAX_CLIENTS_PER_CALL");
@@ -1935,10 +1966,12 @@ he_status he_aggregate(he_ctx* ctx, uint32_t K, const double* alpha_host, const 
   }
   return aggregate_impl(ctx, K, alpha_host, w, ct_in_dev, plain_in_dev, n_ct, n_plain, false, true, acc_ct, acc_plain,
                         ct_out_dev, plain_out_dev, st);
+} catch (...) {
+  return on_exception();
 }
 
 he_status he_aggregate_sum(he_ctx* ctx, uint32_t K, const uint32_t* const* ct_in_dev, const float* const* plain_in_dev,
-                           uint64_t n_ct, uint64_t n_plain, uint32_t* ct_out_dev, float* plain_out_dev, void* stream) {
+                           uint64_t n_ct, uint64_t n_plain, uint32_t* ct_out_dev, float* plain_out_dev, void* stream) try {
   he_status s = check_ctx(ctx);
   if (s != HE_OK) return s;
   if (K == 0 || K > HE_MAX_CLIENTS_PER_CALL) return fail(HE_ERR_INVALID_ARG, "K must be in 1..HE_MAX_CLIENTS_PER_CALL");
@@ -1974,10 +2007,12 @@ he_status he_aggregate_sum(he_ctx* ctx, uint32_t K, const uint32_t* const* ct_in
     done += kc;
   } while (done < K);
   return HE_OK;
+} catch (...) {
+  return on_exception();
 }
 
 he_status he_aggregate_begin(he_ctx* ctx, uint64_t n_ct, uint64_t n_plain, uint32_t* acc_ct_dev, double* acc_plain_dev,
-                             void* stream) {
+                             void* stream) try {
   he_status s = check_ctx(ctx);
   if (s != HE_OK) return s;
   if ((n_ct && !acc_ct_dev) || (n_plain && !acc_plain_dev)) return fail(HE_ERR_INVALID_ARG, "null accumulator");
@@ -1993,11 +2028,13 @@ he_status he_aggregate_begin(he_ctx* ctx, uint64_t n_ct, uint64_t n_plain, uint3
     HIP_TRY(hipGetLastError());
   }
   return HE_OK;
+} catch (...) {
+  return on_exception();
 }
 
 he_status he_aggregate_add(he_ctx* ctx, uint32_t K_chunk, const double* alpha_host, const uint32_t* const* ct_in_dev,
                            const float* const* plain_in_dev, uint64_t n_ct, uint64_t n_plain, uint32_t* acc_ct_dev,
-                           double* acc_plain_dev, void* stream) {
+                           double* acc_plain_dev, void* stream) try {
   he_status s = check_ctx(ctx);
   if (s != HE_OK) return s;
   if (K_chunk == 0 || K_chunk > HE_MAX_CLIENTS_PER_CALL) return fail(HE_ERR_INVALID_ARG, "K_chunk must be in 1..HE_MAX_CLIENTS_PER_CALL");
@@ -2010,10 +2047,12 @@ he_status he_aggregate_add(he_ctx* ctx, uint32_t K_chunk, const double* alpha_ho
   if (s != HE_OK) return s;
   return aggregate_impl(ctx, K_chunk, alpha_host, w, ct_in_dev, plain_in_dev, n_ct, n_plain, true, false, acc_ct_dev,
                         acc_plain_dev, nullptr, nullptr, static_cast<hipStream_t>(stream));
+} catch (...) {
+  return on_exception();
 }
 
 he_status he_aggregate_finalize(he_ctx* ctx, uint64_t n_ct, uint64_t n_plain, const uint32_t* acc_ct_dev,
-                                const double* acc_plain_dev, uint32_t* ct_out_dev, float* plain_out_dev, void* stream) {
+                                const double* acc_plain_dev, uint32_t* ct_out_dev, float* plain_out_dev, void* stream) try {
   he_status s = check_ctx(ctx);
   if (s != HE_OK) return s;
   if ((n_ct && (!acc_ct_dev || !ct_out_dev)) || (n_plain && (!acc_plain_dev || !plain_out_dev)))
@@ -2024,12 +2063,14 @@ he_status he_aggregate_finalize(he_ctx* ctx, uint64_t n_ct, uint64_t n_plain, co
   s = launch_agg(ctx, true, true, a, n_ct, acc_ct_dev, ct_out_dev, st);
   if (s != HE_OK) return s;
   return launch_plain(ctx, true, true, pa, n_plain, acc_plain_dev, nullptr, plain_out_dev, st);
+} catch (...) {
+  return on_exception();
 }
 
 // ---- client: decrypt + merge -----------------------------------------------------------
 
 static he_status decrypt_merge_impl(he_ctx* ctx, const he_sk* sk, const he_mask* mask, uint32_t level,
-                                    const uint32_t* ct_glob_dev, const float* plain_glob_dev, float* w_out_dev, void* stream) {
+                                    const uint32_t* ct_glob_dev, const float* plain_glob_dev, float* w_out_dev, void* stream) try {
   he_status s = check_ctx(ctx);
   if (s != HE_OK) return s;
   if (!sk || !mask || sk->ctx != ctx || mask->ctx != ctx) return fail(HE_ERR_INVALID_ARG, "key/mask missing or from another context");
@@ -2066,22 +2107,28 @@ static he_status decrypt_merge_impl(he_ctx* ctx, const he_sk* sk, const he_mask*
   }
   if (beside) return side_join(ctx, st);
   return HE_OK;
+} catch (...) {
+  return on_exception();
 }
 
 he_status he_decrypt_merge(he_ctx* ctx, const he_sk* sk, const he_mask* mask, const uint32_t* ct_glob_dev,
-                           const float* plain_glob_dev, float* w_out_dev, void* stream) {
+                           const float* plain_glob_dev, float* w_out_dev, void* stream) try {
   if (!ctx) return fail(HE_ERR_INVALID_ARG, "context is null");
   return decrypt_merge_impl(ctx, sk, mask, ctx->ring.L - 1, ct_glob_dev, plain_glob_dev, w_out_dev, stream);
+} catch (...) {
+  return on_exception();
 }
 
 he_status he_decrypt_merge_level(he_ctx* ctx, const he_sk* sk, const he_mask* mask, uint32_t level,
-                                 const uint32_t* ct_glob_dev, const float* plain_glob_dev, float* w_out_dev, void* stream) {
+                                 const uint32_t* ct_glob_dev, const float* plain_glob_dev, float* w_out_dev, void* stream) try {
   return decrypt_merge_impl(ctx, sk, mask, level, ct_glob_dev, plain_glob_dev, w_out_dev, stream);
+} catch (...) {
+  return on_exception();
 }
 
 // ---- test / measurement exports ---------------------------------------------------------
 
-he_status he_debug_encode(he_ctx* ctx, const float* slots_dev, uint64_t n_ct, int32_t* m_out_dev, void* stream) {
+he_status he_debug_encode(he_ctx* ctx, const float* slots_dev, uint64_t n_ct, int32_t* m_out_dev, void* stream) try {
   he_status s = check_ctx(ctx);
   if (s != HE_OK) return s;
   if (n_ct == 0) return HE_OK;
@@ -2089,10 +2136,12 @@ he_status he_debug_encode(he_ctx* ctx, const float* slots_dev, uint64_t n_ct, in
   if (n_ct >= (1ull << 31)) return fail(HE_ERR_INVALID_ARG, "too many ciphertexts");
   MaskDev mk{};
   return launch_encode(ctx, mk, nullptr, slots_dev, 0, n_ct, m_out_dev, nullptr, 0, 0, static_cast<hipStream_t>(stream));
+} catch (...) {
+  return on_exception();
 }
 
 he_status he_debug_encrypt_plain(he_ctx* ctx, const he_pk* pk, uint64_t seed, uint32_t client_id, uint64_t first_ct,
-                                 const int32_t* m_dev, uint64_t n_ct, uint32_t* ct_out_dev, void* stream) {
+                                 const int32_t* m_dev, uint64_t n_ct, uint32_t* ct_out_dev, void* stream) try {
   he_status s = check_ctx(ctx);
   if (s != HE_OK) return s;
   if (n_ct == 0) return HE_OK;
@@ -2114,10 +2163,12 @@ he_status he_debug_encrypt_plain(he_ctx* ctx, const he_pk* pk, uint64_t seed, ui
     if (s != HE_OK) return s;
   }
   return HE_OK;
+} catch (...) {
+  return on_exception();
 }
 
 he_status he_debug_decrypt_residues(he_ctx* ctx, const he_sk* sk, const uint32_t* ct_dev, uint64_t n_ct, uint32_t level,
-                                    uint32_t* d_out_dev, void* stream) {
+                                    uint32_t* d_out_dev, void* stream) try {
   he_status s = check_ctx(ctx);
   if (s != HE_OK) return s;
   if (n_ct == 0) return HE_OK;
@@ -2133,10 +2184,12 @@ he_status he_debug_decrypt_residues(he_ctx* ctx, const he_sk* sk, const uint32_t
     return HE_OK;
   }
   return launch_decrypt(ctx, sk, ct_dev, n_ct, level, d_out_dev, static_cast<hipStream_t>(stream));
+} catch (...) {
+  return on_exception();
 }
 
 he_status he_debug_decode(he_ctx* ctx, const uint32_t* d_dev, uint64_t n_ct, uint32_t level, double* slots_out_dev,
-                          void* stream) {
+                          void* stream) try {
   he_status s = check_ctx(ctx);
   if (s != HE_OK) return s;
   if (n_ct == 0) return HE_OK;
@@ -2145,9 +2198,11 @@ he_status he_debug_decode(he_ctx* ctx, const uint32_t* d_dev, uint64_t n_ct, uin
   if (n_ct >= (1ull << 31)) return fail(HE_ERR_INVALID_ARG, "too many ciphertexts");
   MaskDev mk{};
   return launch_decode(ctx, level, mk, d_dev, 0, n_ct, nullptr, slots_out_dev, static_cast<hipStream_t>(stream));
+} catch (...) {
+  return on_exception();
 }
 
-he_status he_debug_ntt(he_ctx* ctx, int inverse, uint32_t limb, uint32_t* polys_dev, uint64_t batch, void* stream) {
+he_status he_debug_ntt(he_ctx* ctx, int inverse, uint32_t limb, uint32_t* polys_dev, uint64_t batch, void* stream) try {
   he_status s = check_ctx(ctx);
   if (s != HE_OK) return s;
   if (batch == 0) return HE_OK;
@@ -2160,10 +2215,12 @@ he_status he_debug_ntt(he_ctx* ctx, int inverse, uint32_t limb, uint32_t* polys_
   launch_ntt_batch(rg, inverse != 0, (int)limb, polys_dev, (uint32_t)batch, st);
   HIP_TRY(hipGetLastError());
   return HE_OK;
+} catch (...) {
+  return on_exception();
 }
 
 he_status he_debug_export_keys(he_ctx* ctx, const he_pk* pk, const he_sk* sk, uint32_t* pk_coeff_dev, int32_t* sk_coeff_dev,
-                               void* stream) {
+                               void* stream) try {
   he_status s = check_ctx(ctx);
   if (s != HE_OK) return s;
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -2180,19 +2237,23 @@ he_status he_debug_export_keys(he_ctx* ctx, const he_pk* pk, const he_sk* sk, ui
     HIP_TRY(hipGetLastError());
   }
   return HE_OK;
+} catch (...) {
+  return on_exception();
 }
 
-he_status he_debug_timing_enable(he_ctx* ctx, int on) {
+he_status he_debug_timing_enable(he_ctx* ctx, int on) try {
   if (!ctx) return fail(HE_ERR_INVALID_ARG, "context is null");
   ctx->timing_on = on != 0;
   return HE_OK;
+} catch (...) {
+  return on_exception();
 }
 
 uint32_t he_debug_timing_kernels(void) { return KID_COUNT; }
 
 const char* he_debug_timing_name(uint32_t kernel_id) { return kernel_id < KID_COUNT ? kKernelNames[kernel_id] : ""; }
 
-he_status he_debug_timing_read(he_ctx* ctx, double* ms_host, uint64_t* launches_host) {
+he_status he_debug_timing_read(he_ctx* ctx, double* ms_host, uint64_t* launches_host) try {
   he_status s = check_ctx(ctx);
   if (s != HE_OK) return s;
   if (!ms_host || !launches_host) return fail(HE_ERR_INVALID_ARG, "null argument");
@@ -2211,6 +2272,8 @@ he_status he_debug_timing_read(he_ctx* ctx, double* ms_host, uint64_t* launches_
   }
   ctx->spans.clear();
   return HE_OK;
+} catch (...) {
+  return on_exception();
 }
 
 }  // extern "C"
