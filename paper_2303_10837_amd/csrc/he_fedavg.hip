@@ -1054,7 +1054,11 @@ class KernelTimer {
     live_ = span_.start && span_.stop && hipEventRecord(span_.start, st_) == hipSuccess;
   }
   ~KernelTimer() {
-    if (live_ && hipEventRecord(span_.stop, st_) == hipSuccess) ctx_->spans.push_back(span_);
+    if (!live_ || hipEventRecord(span_.stop, st_) != hipSuccess) return;
+    try {
+      ctx_->spans.push_back(span_);
+    } catch (...) {  // a destructor must not throw: this span is dropped from the measurement
+    }
   }
 
  private:
@@ -1676,11 +1680,18 @@ he_status he_mask_create(he_ctx* ctx, uint64_t P, const uint64_t* starts, const 
   }
   pf_v.push_back(packed);
   cp_v.push_back(cpacked);
+  const size_t o_st = 0, o_pf = o_st + st_v.size() + 1, o_cs = o_pf + pf_v.size(), o_cp = o_cs + cs_v.size() + 1;
+  block.assign(o_cp + cp_v.size(), 0);
   he_mask* mk = new (std::nothrow) he_mask();
   if (!mk) return fail(HE_ERR_NOMEM, "host allocation failed");
   mk->ctx = ctx;
-  const size_t o_st = 0, o_pf = o_st + st_v.size() + 1, o_cs = o_pf + pf_v.size(), o_cp = o_cs + cs_v.size() + 1;
-  block.assign(o_cp + cp_v.size(), 0);
+  try {  // the host copy of the run list is the last thing that can throw
+    mk->starts.assign(starts, starts + n_runs);
+    mk->lens.assign(lens, lens + n_runs);
+  } catch (...) {
+    he_mask_destroy(mk);
+    return on_exception();
+  }
   std::copy(st_v.begin(), st_v.end(), block.begin() + o_st);
   std::copy(pf_v.begin(), pf_v.end(), block.begin() + o_pf);
   std::copy(cs_v.begin(), cs_v.end(), block.begin() + o_cs);
@@ -1700,8 +1711,6 @@ he_status he_mask_create(he_ctx* ctx, uint64_t P, const uint64_t* starts, const 
   mk->dev.n_cruns = (uint32_t)cs_v.size();
   mk->dev.P = P;
   mk->dev.P_enc = packed;
-  mk->starts.assign(starts, starts + n_runs);
-  mk->lens.assign(lens, lens + n_runs);
   *out = mk;
   return HE_OK;
 } catch (...) {
@@ -1750,7 +1759,14 @@ static he_status mask_from_device_bytes(he_ctx* ctx, uint64_t P, const uint8_t* 
     cleanup();
     return fail(HE_ERR_HIP, "run extraction: starts and ends disagree");
   }
-  std::vector<uint64_t> starts(R), lens(R);
+  std::vector<uint64_t> starts, lens;
+  try {
+    starts.resize(R);
+    lens.resize(R);
+  } catch (...) {
+    cleanup();
+    return on_exception();
+  }
   if (R) {
     MK_TRY(hipMalloc(&runs_dev, 2 * R * sizeof(uint64_t)));
     hipLaunchKernelGGL(k_runs<true>, dim3((uint32_t)n_chunks), dim3(kThreads), 0, st, mask_dev, P, nullptr, nullptr, off_start, off_end,
