@@ -237,6 +237,13 @@ he_status he_debug_ntt(he_ctx* ctx, int inverse, uint32_t limb, uint32_t* polys_
 he_status he_debug_export_keys(he_ctx* ctx, const he_pk* pk, const he_sk* sk,
                                uint32_t* pk_coeff_dev, int32_t* sk_coeff_dev, void* stream);
 
+/* Precondition check for he_encrypt_masked (which does not validate on the hot path): counts the
+   entries of w_dev float32[n] that are not finite or whose magnitude times Delta reaches
+   2^31 - 32, so that plaintext plus error would leave 32 bits.  Synchronous on `stream`; uses the
+   context's scratch like every other call. */
+he_status he_debug_count_out_of_range(he_ctx* ctx, const float* w_dev, uint64_t n,
+                                      uint64_t* count_host, void* stream);
+
 /* Per-kernel device timing for benchmarks: while enabled, every kernel launch of this
    context is bracketed by a pair of HIP events on its stream.  he_debug_timing_read waits
    for the recorded events, writes the summed milliseconds and the launch count of each

@@ -64,6 +64,7 @@ _SIGS = {
     "he_debug_decode": (C.c_int32, [_P, _P, C.c_uint64, C.c_uint32, _P, _P]),
     "he_debug_ntt": (C.c_int32, [_P, C.c_int, C.c_uint32, _P, C.c_uint64, _P]),
     "he_debug_export_keys": (C.c_int32, [_P, _P, _P, _P, _P, _P]),
+    "he_debug_count_out_of_range": (C.c_int32, [_P, _P, C.c_uint64, C.POINTER(C.c_uint64), _P]),
     "he_debug_timing_enable": (C.c_int32, [_P, C.c_int]),
     "he_debug_timing_kernels": (C.c_uint32, []),
     "he_debug_timing_name": (C.c_char_p, [C.c_uint32]),
@@ -364,6 +365,12 @@ def he_debug_export_keys(ctx, keys):
     sk = torch.empty((ctx.N,), dtype=torch.int32, device=ctx.device)
     _check(load().he_debug_export_keys(ctx.h, keys.pk, keys.sk, _ptr(pk), _ptr(sk), _stream()))
     return pk, sk
+
+
+def he_debug_count_out_of_range(ctx, w):
+    n = C.c_uint64(0)
+    _check(load().he_debug_count_out_of_range(ctx.h, _ptr(w, torch.float32) if w.numel() else None, w.numel(), C.byref(n), _stream()))
+    return int(n.value)
 
 
 def he_debug_timing_enable(ctx, on):

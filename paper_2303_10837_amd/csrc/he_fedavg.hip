@@ -958,6 +958,19 @@ __global__ void __launch_bounds__(256) k_widen_i8(const int8_t* __restrict__ in,
   if (i < n) out[i] = in[i];
 }
 
+// Counts the parameters the encoder cannot carry: not finite, or |x| * Delta >= 2^31 - 32 (m + e0 would leave int32).
+__global__ void __launch_bounds__(256)
+k_count_out_of_range(const float* __restrict__ w, uint64_t n, double delta, unsigned long long* __restrict__ count) {
+  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+  uint32_t bad = 0;
+  for (uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; t < n; t += stride) {
+    const double x = (double)w[t];
+    if (!(fabs(x) * delta < 2147483616.0)) ++bad;  // exact in float64; NaN compares false: counted
+  }
+  for (int d = 32; d > 0; d >>= 1) bad += __shfl_down(bad, d, 64);
+  if ((threadIdx.x & 63) == 0 && bad) atomicAdd(count, (unsigned long long)bad);
+}
+
 // =========================================================================================
 // Host side
 // =========================================================================================
@@ -2252,6 +2265,29 @@ he_status he_debug_export_keys(he_ctx* ctx, const he_pk* pk, const he_sk* sk, ui
     hipLaunchKernelGGL(k_widen_i8, dim3((rg.N + 255) / 256), dim3(256), 0, st, sk->coeff, sk_coeff_dev, rg.N);
     HIP_TRY(hipGetLastError());
   }
+  return HE_OK;
+} catch (...) {
+  return on_exception();
+}
+
+he_status he_debug_count_out_of_range(he_ctx* ctx, const float* w_dev, uint64_t n, uint64_t* count_host, void* stream) try {
+  he_status s = check_ctx(ctx);
+  if (s != HE_OK) return s;
+  if (!count_host || (n && !w_dev)) return fail(HE_ERR_INVALID_ARG, "null argument");
+  *count_host = 0;
+  if (n == 0) return HE_OK;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  s = ensure_ws(ctx, 256);
+  if (s != HE_OK) return s;
+  unsigned long long* cnt = static_cast<unsigned long long*>(ctx->ws);
+  hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, reinterpret_cast<uint32_t*>(cnt), (uint64_t)2, 0u);
+  hipLaunchKernelGGL(k_count_out_of_range, dim3(grid_for(n, 256, 4096)), dim3(256), 0, st, w_dev, n,
+                     std::ldexp(1.0, (int)ctx->ring.scale_bits), cnt);
+  HIP_TRY(hipGetLastError());
+  unsigned long long host = 0;
+  HIP_TRY(hipMemcpyAsync(&host, cnt, sizeof(host), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  *count_host = host;
   return HE_OK;
 } catch (...) {
   return on_exception();

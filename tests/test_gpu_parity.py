@@ -433,3 +433,19 @@ def test_mask_from_bytes_and_errors(he):
         he.Context(16, 3)
     with pytest.raises(he.HeError):
         he.Context(10, 1)
+
+
+def test_input_range_check(he):
+    """he_debug_count_out_of_range counts exactly the entries the encoder cannot carry."""
+    ctx, _, p, _ = _setup(he, 10, 3)
+    rs = np.random.default_rng(11)
+    w = rs.normal(0, 0.05, 300_001).astype(np.float32)
+    assert he.he_debug_count_out_of_range(ctx, _dev(w)) == 0
+    bad = {5: np.nan, 17: np.inf, 99: -np.inf, 1000: 2.0, 2000: -2.0, 300_000: 1e30}
+    fine = {7: np.float32(2.0) - np.float32(2.0 ** -22), 8: -(np.float32(2.0) - np.float32(2.0 ** -22)), 9: 0.0, 10: -0.0}
+    for k, v in {**bad, **fine}.items():
+        w[k] = v
+    ref = int(np.sum(~(np.abs(w.astype(np.float64)) * 2.0 ** 30 < 2.0 ** 31 - 32)))
+    assert ref == len(bad)
+    assert he.he_debug_count_out_of_range(ctx, _dev(w)) == ref
+    assert he.he_debug_count_out_of_range(ctx, torch.empty(0, dtype=torch.float32, device="cuda")) == 0
