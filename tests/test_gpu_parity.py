@@ -449,3 +449,26 @@ def test_input_range_check(he):
     assert ref == len(bad)
     assert he.he_debug_count_out_of_range(ctx, _dev(w)) == ref
     assert he.he_debug_count_out_of_range(ctx, torch.empty(0, dtype=torch.float32, device="cuda")) == 0
+
+
+@pytest.mark.parametrize("log2_n,limbs", [(10, 3), (13, 3)])
+def test_degenerate_sizes(he, log2_n, limbs):
+    """The smallest inputs: an empty model, one parameter (encrypted, or left plain), one parameter more than a ciphertext."""
+    ctx, keys, p, okeys = _setup(he, log2_n, limbs)
+    n = p.n_slots
+    alpha = np.array([0.25, 0.75])
+    for P, runs in ((0, []), (1, [(0, 1)]), (1, []), (n + 1, [(0, n + 1)]), (2, [(1, 1)])):
+        mask = he.he_mask_create(ctx, P, [r[0] for r in runs], [r[1] for r in runs])
+        enc_idx, plain_idx = ofed.mask_indices(P, runs)
+        assert mask.P == P and mask.P_enc == len(enc_idx) and mask.n_ct == ofed.n_ciphertexts(p, len(enc_idx))
+        rs = np.random.default_rng(P + len(runs))
+        ws = [rs.normal(0, 0.05, P).astype(np.float32) for _ in range(2)]
+        cts, plains, ct_g, pl_g, out = _gpu_round(he, ctx, keys, mask, [_dev(w) for w in ws], alpha, SEED)
+        out = _np(out)
+        assert out.shape == (P,)
+        expect = ofed.secure_round(p, okeys, ws, alpha, runs, SEED)
+        # the GPU's encoder may differ from the oracle's by one unit in a coefficient: 2^-30 in a slot at most n times over
+        assert np.array_equal(out[plain_idx], expect[plain_idx])
+        if len(enc_idx):
+            assert np.abs(out[enc_idx].astype(np.float64) - expect[enc_idx].astype(np.float64)).max() <= 1e-6
+        mask.close()
