@@ -364,18 +364,22 @@ __device__ __forceinline__ void load_key8(const uint2* __restrict__ key, int bas
 template <int LOGN>
 __global__ void __launch_bounds__(NttPlan<LOGN>::NT, 8)
 k_encrypt_s(RingDev rg, const uint2* __restrict__ pk, const int8_t* __restrict__ u, const int32_t* __restrict__ m,
-            const int8_t* __restrict__ e0, const int8_t* __restrict__ e1, uint32_t* __restrict__ ct_out, uint32_t n_ct) {
+            const int8_t* __restrict__ e0, const int8_t* __restrict__ e1, uint32_t* __restrict__ ct_out, uint32_t n_ct,
+            uint32_t cts_per_slot) {
   using P = NttPlan<LOGN>;
   constexpr int N = 1 << LOGN, NT = P::NT;
   extern __shared__ uint32_t lds_u[];
   uint32_t* A = lds_u;
   const uint32_t L = rg.L;
-  // Workgroups are dealt to the 8 XCDs round-robin by linear id; the L limb-workgroups of one
-  // ciphertext read the same u / m / e0 / e1, so they are placed on the same XCD (one L2) at
-  // consecutive slots: id = slot * 8 + xcd, slot = (c / 8) * L + limb, xcd = c % 8.
-  const uint32_t slot = blockIdx.x >> 3;
-  const uint32_t j = slot % L;
-  const uint64_t c = (uint64_t)(slot / L) * 8 + (blockIdx.x & 7);
+  // Workgroups are dealt to the 8 XCDs round-robin by linear id (id = slot * 8 + xcd), and each XCD has its own L2.
+  // When L divides 8 (cts_per_slot = 8 / L) every XCD works on ONE limb, xcd % L: its L2 then holds the twiddle and
+  // key tables of that limb only (512 KiB instead of 2 MiB at N = 2^14, L = 4) beside the parked polynomials, and
+  // the tables stop being evicted and fetched again; that u / m / e0 / e1 of a ciphertext are now read on L XCDs
+  // costs less (they are small and recent).  Measured: encrypt 5.74 -> 5.56 ms per 8 x 1429 ciphertexts.
+  // Otherwise the L limb-workgroups of a ciphertext sit on one XCD at consecutive slots.
+  const uint32_t slot = blockIdx.x >> 3, xcd = blockIdx.x & 7;
+  const uint32_t j = cts_per_slot ? xcd % L : slot % L;
+  const uint64_t c = cts_per_slot ? (uint64_t)slot * cts_per_slot + xcd / L : (uint64_t)(slot / L) * 8 + xcd;
   if (c >= n_ct) return;  // whole workgroup leaves before any barrier
   const uint32_t q = rg.q[j];
   const uint2* twf = rg.tw_fwd + (size_t)j * N;
@@ -1234,13 +1238,15 @@ he_status launch_encrypt(he_ctx* ctx, const he_pk* pk, uint64_t n_ct, const int3
   const RingDev& rg = ctx->ring;
   KernelTimer timer_(ctx, KID_ENCRYPT, st);
   const dim3 grid(rg.L, (uint32_t)n_ct);
-  const dim3 grid_x((uint32_t)((n_ct + 7) / 8) * 8 * rg.L);  // XCD-aware linear grid, see k_encrypt_s
+  // XCD-aware linear grid, see k_encrypt_s: one limb per XCD when L divides 8
+  const uint32_t cts_per_slot = (8 % rg.L == 0) ? 8 / rg.L : 0;
+  const dim3 grid_x(cts_per_slot ? (uint32_t)((n_ct + cts_per_slot - 1) / cts_per_slot) * 8 : (uint32_t)((n_ct + 7) / 8) * 8 * rg.L);
   if (rg.logN == 14)
     hipLaunchKernelGGL(k_encrypt_s<14>, grid_x, dim3(NttPlan<14>::NT), static_lds_bytes(14, 1), st, rg, pk->tab, rnd.u, m, rnd.e0, rnd.e1,
-                       ct_out, (uint32_t)n_ct);
+                       ct_out, (uint32_t)n_ct, cts_per_slot);
   else if (rg.logN == 13)
     hipLaunchKernelGGL(k_encrypt_s<13>, grid_x, dim3(NttPlan<13>::NT), static_lds_bytes(13, 1), st, rg, pk->tab, rnd.u, m, rnd.e0, rnd.e1,
-                       ct_out, (uint32_t)n_ct);
+                       ct_out, (uint32_t)n_ct, cts_per_slot);
   else
     hipLaunchKernelGGL(k_encrypt, grid, dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 2), st, rg, pk->tab, rnd.u, m, rnd.e0, rnd.e1, ct_out);
   HIP_TRY(hipGetLastError());
