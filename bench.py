@@ -226,6 +226,8 @@ def main():
                     help="fold each client's plaintext remainder into the server's accumulator right after its encryption "
                          "(he_aggregate_begin/add/finalize) and keep only 4 distinct client vectors resident; chosen by "
                          "itself when the clients' vectors exceed 64 GB")
+    ap.add_argument("--fold-group", type=int, default=16, help="streamed clients: remainders the server folds per he_aggregate_add")
+    ap.add_argument("--fold-buffers", type=int, default=1, help="streamed clients: groups of remainder buffers (2 = the next group encrypts while one is folded)")
     ap.add_argument("--client-streams", type=int, default=1,
                     help="number of clients that encrypt side by side, each on its own context and stream (default 1: one after the other)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -274,16 +276,18 @@ def main():
     pl_g = torch.empty((n_pl,), dtype=torch.float32, device="cuda")
     out = torch.empty((w.n_params,), dtype=torch.float32, device="cuda")
     # The server is its own party with its own copy of the public crypto context (it never holds a key).  In the
-    # streamed form it works on a second stream beside the clients: it folds the plaintext remainders of G clients at
-    # a time into its float64 accumulator while the next clients encrypt (HBM-bound beside ALU-bound work).
+    # streamed form it works on a second stream and folds the plaintext remainders of G clients at a time into its
+    # float64 accumulator (one read-modify-write of the accumulator per G clients).  With one set of G buffers the
+    # clients wait for the fold before they reuse a buffer; a second set lets them go on, which gains nothing here
+    # (the fold and the encryption kernels share the memory system) and costs the memory a larger G can use.
     acc_none = acc_plain = ct_none = server = server_stream = None
-    G = 4
+    G, N_HALVES = args.fold_group, args.fold_buffers
     if streamed:
         if client_weighted:
             sys.exit("bench.py: --variant client_weighted is not combined with streamed clients")
         server = he.Context(w.log2_n, n_limbs, w.scale_bits, w.cbd_eta)
         server_stream = torch.cuda.Stream()
-        plains = [torch.empty((n_pl,), dtype=torch.float32, device="cuda") for _ in range(min(K, 2 * G))]
+        plains = [torch.empty((n_pl,), dtype=torch.float32, device="cuda") for _ in range(min(K, N_HALVES * G))]
         acc_none, acc_plain = he.he_aggregate_begin(server, 0, n_pl)
         ct_none = torch.empty((0, 2, L_out, N), dtype=torch.int32, device="cuda")
         torch.cuda.synchronize()
@@ -301,7 +305,7 @@ def main():
         folded = {}                                    # buffer half -> event: the server has read these remainders
         for g0 in range(0, K, G):
             grp = list(range(g0, min(g0 + G, K)))
-            half = (g0 // G) % 2
+            half = (g0 // G) % N_HALVES
             if half in folded:
                 cur.wait_event(folded[half])
             slots = [half * G + (i - g0) for i in grp]
@@ -446,6 +450,9 @@ def main():
     select_rows = mask_select_bench(he, ctx, torch) if args.select_bench else None
 
     # sanity: the decoded aggregate is FedAvg up to the CKKS noise (not part of the timing)
+    if streamed:
+        plains.clear()
+        torch.cuda.empty_cache()
     ref = sum(float(a) * x.double() for a, x in zip(alpha, ws))
     max_err = float((out.double() - ref).abs().max())
 
