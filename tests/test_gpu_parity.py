@@ -472,3 +472,38 @@ def test_degenerate_sizes(he, log2_n, limbs):
         if len(enc_idx):
             assert np.abs(out[enc_idx].astype(np.float64) - expect[enc_idx].astype(np.float64)).max() <= 1e-6
         mask.close()
+
+
+def test_three_training_rounds(he):
+    """Algorithm 1's loop, T = 3 rounds with one context, key pair and mask: decrypt + merge, a stand-in for local
+    training (every client adds its own small update), encrypt, aggregate.  Each round is checked against the oracle's
+    round on the same inputs, and the final model against the float64 FedAvg recursion under the noise model (fresh
+    noise every round: the per-round seeds differ, so three independent errors add up)."""
+    ctx, keys, p, okeys = _setup(he, 13, 3)
+    n = p.n_slots
+    P = 3 * n + 500
+    runs = [(100, n + 50), (2 * n, n // 2)]
+    mask = he.he_mask_create(ctx, P, [r[0] for r in runs], [r[1] for r in runs])
+    enc_idx, _ = ofed.mask_indices(P, runs)
+    K = 3
+    alpha = np.array([0.2, 0.3, 0.5])
+    rs = np.random.default_rng(12)
+    glob_gpu = rs.normal(0, 0.05, P).astype(np.float32)
+    glob_ref = glob_gpu.astype(np.float64)
+    for t in range(3):
+        updates = [rs.normal(0, 0.01, P).astype(np.float32) for _ in range(K)]
+        ws = [(glob_gpu + u).astype(np.float32) for u in updates]                       # "Train"
+        glob_ref = sum(a * (glob_ref + u.astype(np.float64)) for a, u in zip(alpha, updates))
+        seed = SEED + 1000 * t
+        _, _, _, _, out = _gpu_round(he, ctx, keys, mask, [_dev(w) for w in ws], alpha, seed)
+        out = _np(out)
+        expect = ofed.secure_round(p, okeys, ws, alpha, runs, seed)
+        assert np.abs(out.astype(np.float64) - expect.astype(np.float64)).max() <= 1e-6, t
+        glob_gpu = out
+    sigma = ofed.noise_sigma(p, alpha)
+    err = glob_gpu.astype(np.float64) - glob_ref
+    plain = np.setdiff1d(np.arange(P), enc_idx)
+    assert np.abs(err[plain]).max() < 3e-7                                               # float32 rounding of the plain part, three times
+    assert np.abs(err[enc_idx]).max() < 16 * sigma * np.sqrt(3)
+    assert 0.6 * sigma < err[enc_idx].std() < 1.4 * sigma * np.sqrt(3)
+    mask.close()
