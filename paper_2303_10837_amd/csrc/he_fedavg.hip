@@ -657,23 +657,30 @@ k_decode(RingDev rg, CrtArgs ca, MaskDev mk, const uint32_t* __restrict__ d, uin
   }
 }
 
-// ---- specialised decoder: lift fused into the first decimation-in-frequency pass ------------
+// ---- half-length decoder (the tuned sizes): only the REAL part of the n-point transform is wanted, so it is the
+// inverse real transform of the Hermitian part of the input and comes from one n/2-point complex FFT (the encoder's
+// network transposed).  With d_k = (v_k + i v_{k+n}) zeta^k, h = n/2, w = exp(+2 pi i / n):
+//     X_k = (d_k + conj d_{n-k}) / 2,            Y_k = conj X_{h-k} = (conj d_{h-k} + d_{h+k}) / 2,
+//     Z_k = (X_k + Y_k) + i w^k (X_k - Y_k),     Z_{h-k} = conj(X_k + Y_k) + i conj(w^k (X_k - Y_k)),
+//     z_s = sum_{k<h} Z_k exp(+2 pi i s k / h),  Re D[2s] = Re z_s,  Re D[2s+1] = Im z_s.
+// One thread lifts the four inputs of a pair (k, h-k); half the LDS (two workgroups per CU) and half the flops of
+// the full-length form.  The factor 1/2 of X and Y goes into the final scale.
 template <int LOGN, int LEVEL>
-__global__ void __launch_bounds__(FftPlan<LOGN - 1>::NT)
-k_decode_s(RingDev rg, CrtArgs ca, MaskDev mk, const uint32_t* __restrict__ d, uint64_t first_ct,
+__global__ void __launch_bounds__(FftPlan<LOGN - 2>::NT)
+k_decode_h(RingDev rg, CrtArgs ca, MaskDev mk, const uint32_t* __restrict__ d, uint64_t first_ct,
            float* __restrict__ w_out, double* __restrict__ slots_out) {
-  constexpr int LOGn = LOGN - 1, n = 1 << LOGn, N = 1 << LOGN;
-  using P = FftPlan<LOGn>;
+  constexpr int LOGh = LOGN - 2, h = 1 << LOGh, n = 2 * h, N = 4 * h;
+  using P = FftPlan<LOGh>;
   extern __shared__ double lds_d[];
   double* re = lds_d;
-  double* im = lds_d + fpad(n);
+  double* im = lds_d + h;
   const uint64_t c_local = blockIdx.x;
   const uint32_t* dc = d + c_local * LEVEL * N;
-  const double2* e_tab = rg.fft_e;
+  const double2* e_tab = rg.fft_e;  // exp(-2 pi i r / n), r < h
   const double2* twist = rg.twist;
-  auto ldl = [=](int a, double& r, double& i) { r = re[fswz<LOGn>(a)]; i = im[fswz<LOGn>(a)]; };
-  auto stl = [=](int a, double r, double i) { re[fswz<LOGn>(a)] = r; im[fswz<LOGn>(a)] = i; };
-  fft_pass<LOGn, 0, false, true>(e_tab, [&](int k, double& r, double& i) {
+  auto ldl = [=](int a, double& r, double& i) { r = re[fswz<LOGh>(a)]; i = im[fswz<LOGh>(a)]; };
+  auto stl = [=](int a, double r, double i) { re[fswz<LOGh>(a)] = r; im[fswz<LOGh>(a)] = i; };
+  auto lift = [&](int k, double& r, double& i) {  // d_k
     uint32_t ra[LEVEL], rb[LEVEL];
 #pragma unroll
     for (int j = 0; j < LEVEL; ++j) {
@@ -685,19 +692,50 @@ k_decode_s(RingDev rg, CrtArgs ca, MaskDev mk, const uint32_t* __restrict__ d, u
     const double2 tw = twist[k];
     r = vr * tw.x - vi * tw.y;
     i = vr * tw.y + vi * tw.x;
-  }, stl);
-  __syncthreads();
-  fft_pass<LOGn, 1, false, true>(e_tab, ldl, stl);
-  __syncthreads();
-  fft_pass<LOGn, 2, false, true>(e_tab, ldl, stl);
-  __syncthreads();
-  fft_pass<LOGn, 3, false, true>(e_tab, ldl, stl);
-  __syncthreads();
-  if constexpr (P::kPasses == 5) {
-    fft_pass<LOGn, 4, false, true>(e_tab, ldl, stl);
-    __syncthreads();
+  };
+  static_assert((h / 2) % P::NT == 0, "whole iterations over the pairs");
+  for (int k = threadIdx.x; k < h / 2; k += P::NT) {
+    // pair (k, h-k); k = 0 stands for the two self-paired indices 0 and h/2
+    const int ka = k, kb = k ? h - k : h / 2;
+    double ar, ai, br, bi, cr, ci, er, ei;
+    lift(ka, ar, ai);                       // d_k
+    lift((n - ka) & (n - 1), br, bi);       // d_{n-k}
+    if (k) {
+      lift(h - k, cr, ci);                  // d_{h-k}
+      lift(h + k, er, ei);                  // d_{h+k}
+    } else {
+      lift(h / 2, cr, ci);                  // second self-pair: d_{h/2} and d_{3h/2}
+      lift(h + h / 2, er, ei);
+    }
+    if (k) {
+      const double xr = ar + br, xi = ai - bi;            // 2 X_k
+      const double yr = cr + er, yi = ei - ci;            // 2 Y_k
+      const double sr = xr + yr, si = xi + yi;            // 2 (X + Y)
+      const double dr = xr - yr, di = xi - yi;            // 2 (X - Y)
+      const double2 w = e_tab[k];                         // conj(w^k)
+      const double tr = dr * w.x + di * w.y, ti = di * w.x - dr * w.y;   // 2 w^k (X - Y)
+      stl(ka, sr - ti, si + tr);                          // S + i T
+      stl(kb, sr + ti, tr - si);                          // conj S + i conj T
+    } else {
+      // k = 0: d_{n-0} = d_0 and d_{h-0} = d_{h+0} = d_h (here: a = b = d_0 is loaded twice; c, e are the second pair)
+      double hr, hi;
+      lift(h, hr, hi);                                    // d_h
+      stl(0, 2.0 * (ar + hr), 2.0 * (ar - hr));           // Z_0 = (Re d_0 + Re d_h) + i (Re d_0 - Re d_h), doubled
+      // Z_{h/2}: X = (d_{h/2} + conj d_{3h/2}) / 2, S = 2 Re X, T = -2 Im X, doubled like the rest
+      stl(h / 2, 2.0 * (cr + er), -2.0 * (ci - ei));
+    }
   }
-  const double inv_delta = ldexp(1.0, -(int)rg.scale_bits);
+  __syncthreads();
+  fft_pass<LOGh, 0, false, true, 1>(e_tab, ldl, stl);
+  __syncthreads();
+  fft_pass<LOGh, 1, false, true, 1>(e_tab, ldl, stl);
+  __syncthreads();
+  fft_pass<LOGh, 2, false, true, 1>(e_tab, ldl, stl);
+  __syncthreads();
+  fft_pass<LOGh, 3, false, true, 1>(e_tab, ldl, stl);
+  __syncthreads();
+  static_assert(P::kPasses == 4, "plans of the half-length transforms have four passes");
+  const double scale = ldexp(1.0, -(int)rg.scale_bits - 1);  // 1 / Delta and the 1/2 of X, Y
   uint32_t r_lo = 0, r_hi = 0;
   const uint64_t c = first_ct + c_local;
   if (!slots_out) {
@@ -705,7 +743,8 @@ k_decode_s(RingDev rg, CrtArgs ca, MaskDev mk, const uint32_t* __restrict__ d, u
     r_hi = run_find(mk.prefix, mk.n_runs, min((c + 1) * (uint64_t)n, mk.P_enc) - 1);
   }
   for (int j = threadIdx.x; j < n; j += P::NT) {
-    const double z = re[fswz<LOGn>((int)rg.perm_enc[j])] * inv_delta;  // bin t_j sits at bitrev(t_j)
+    const uint32_t code = rg.perm_half[j];  // (bitrev(bin >> 1) << 1) | (bin & 1): bin 2s at Re z_s, bin 2s+1 at Im z_s
+    const double z = ((code & 1) ? im : re)[fswz<LOGh>((int)(code >> 1))] * scale;
     if (slots_out) {
       slots_out[c_local * n + j] = z;
     } else {
@@ -1337,10 +1376,10 @@ void launch_decode_t(he_ctx* ctx, const CrtArgs& ca, const MaskDev& mk, const ui
                      float* w_out, double* slots_out, hipStream_t st) {
   const uint32_t n = ctx->ring.N / 2;
   if (ctx->ring.logN == 14)
-    hipLaunchKernelGGL((k_decode_s<14, LEVEL>), dim3((uint32_t)n_ct), dim3(FftPlan<13>::NT), static_fft_lds_bytes(13), st, ctx->ring,
+    hipLaunchKernelGGL((k_decode_h<14, LEVEL>), dim3((uint32_t)n_ct), dim3(FftPlan<12>::NT), static_fft_lds_bytes(12), st, ctx->ring,
                        ca, mk, d, first_ct, w_out, slots_out);
   else if (ctx->ring.logN == 13)
-    hipLaunchKernelGGL((k_decode_s<13, LEVEL>), dim3((uint32_t)n_ct), dim3(FftPlan<12>::NT), static_fft_lds_bytes(12), st, ctx->ring,
+    hipLaunchKernelGGL((k_decode_h<13, LEVEL>), dim3((uint32_t)n_ct), dim3(FftPlan<11>::NT), static_fft_lds_bytes(11), st, ctx->ring,
                        ca, mk, d, first_ct, w_out, slots_out);
   else
     hipLaunchKernelGGL(k_decode<LEVEL>, dim3((uint32_t)n_ct), dim3(fft_threads(n)), fft_lds_bytes(n), st, ctx->ring, ca, mk, d,
@@ -1595,23 +1634,23 @@ he_status he_ctx_create(const he_params* params, int device, he_ctx** out) try {
   if (s == HE_OK && logN == 13) s = allow_lds(k_ntt_batch_s<13, false>, static_lds_bytes(13, 1));
   if (s == HE_OK && logN == 13) s = allow_lds(k_ntt_batch_s<13, true>, static_lds_bytes(13, 1));
   if (s == HE_OK && logN == 14) s = allow_lds(k_encode_r<14>, static_fft_lds_bytes(12));
-  if (s == HE_OK && logN == 14) s = allow_lds(k_decode_s<14, 1>, static_fft_lds_bytes(13));
-  if (s == HE_OK && logN == 14) s = allow_lds(k_decode_s<14, 2>, static_fft_lds_bytes(13));
-  if (s == HE_OK && logN == 14) s = allow_lds(k_decode_s<14, 3>, static_fft_lds_bytes(13));
-  if (s == HE_OK && logN == 14) s = allow_lds(k_decode_s<14, 4>, static_fft_lds_bytes(13));
-  if (s == HE_OK && logN == 14) s = allow_lds(k_decode_s<14, 5>, static_fft_lds_bytes(13));
-  if (s == HE_OK && logN == 14) s = allow_lds(k_decode_s<14, 6>, static_fft_lds_bytes(13));
-  if (s == HE_OK && logN == 14) s = allow_lds(k_decode_s<14, 7>, static_fft_lds_bytes(13));
-  if (s == HE_OK && logN == 14) s = allow_lds(k_decode_s<14, 8>, static_fft_lds_bytes(13));
+  if (s == HE_OK && logN == 14) s = allow_lds(k_decode_h<14, 1>, static_fft_lds_bytes(12));
+  if (s == HE_OK && logN == 14) s = allow_lds(k_decode_h<14, 2>, static_fft_lds_bytes(12));
+  if (s == HE_OK && logN == 14) s = allow_lds(k_decode_h<14, 3>, static_fft_lds_bytes(12));
+  if (s == HE_OK && logN == 14) s = allow_lds(k_decode_h<14, 4>, static_fft_lds_bytes(12));
+  if (s == HE_OK && logN == 14) s = allow_lds(k_decode_h<14, 5>, static_fft_lds_bytes(12));
+  if (s == HE_OK && logN == 14) s = allow_lds(k_decode_h<14, 6>, static_fft_lds_bytes(12));
+  if (s == HE_OK && logN == 14) s = allow_lds(k_decode_h<14, 7>, static_fft_lds_bytes(12));
+  if (s == HE_OK && logN == 14) s = allow_lds(k_decode_h<14, 8>, static_fft_lds_bytes(12));
   if (s == HE_OK && logN == 13) s = allow_lds(k_encode_r<13>, static_fft_lds_bytes(11));
-  if (s == HE_OK && logN == 13) s = allow_lds(k_decode_s<13, 1>, static_fft_lds_bytes(12));
-  if (s == HE_OK && logN == 13) s = allow_lds(k_decode_s<13, 2>, static_fft_lds_bytes(12));
-  if (s == HE_OK && logN == 13) s = allow_lds(k_decode_s<13, 3>, static_fft_lds_bytes(12));
-  if (s == HE_OK && logN == 13) s = allow_lds(k_decode_s<13, 4>, static_fft_lds_bytes(12));
-  if (s == HE_OK && logN == 13) s = allow_lds(k_decode_s<13, 5>, static_fft_lds_bytes(12));
-  if (s == HE_OK && logN == 13) s = allow_lds(k_decode_s<13, 6>, static_fft_lds_bytes(12));
-  if (s == HE_OK && logN == 13) s = allow_lds(k_decode_s<13, 7>, static_fft_lds_bytes(12));
-  if (s == HE_OK && logN == 13) s = allow_lds(k_decode_s<13, 8>, static_fft_lds_bytes(12));
+  if (s == HE_OK && logN == 13) s = allow_lds(k_decode_h<13, 1>, static_fft_lds_bytes(11));
+  if (s == HE_OK && logN == 13) s = allow_lds(k_decode_h<13, 2>, static_fft_lds_bytes(11));
+  if (s == HE_OK && logN == 13) s = allow_lds(k_decode_h<13, 3>, static_fft_lds_bytes(11));
+  if (s == HE_OK && logN == 13) s = allow_lds(k_decode_h<13, 4>, static_fft_lds_bytes(11));
+  if (s == HE_OK && logN == 13) s = allow_lds(k_decode_h<13, 5>, static_fft_lds_bytes(11));
+  if (s == HE_OK && logN == 13) s = allow_lds(k_decode_h<13, 6>, static_fft_lds_bytes(11));
+  if (s == HE_OK && logN == 13) s = allow_lds(k_decode_h<13, 7>, static_fft_lds_bytes(11));
+  if (s == HE_OK && logN == 13) s = allow_lds(k_decode_h<13, 8>, static_fft_lds_bytes(11));
   if (s == HE_OK) s = allow_lds(k_decode<1>, fft_lds_bytes(n));
   if (s == HE_OK) s = allow_lds(k_decode<2>, fft_lds_bytes(n));
   if (s == HE_OK) s = allow_lds(k_decode<3>, fft_lds_bytes(n));
