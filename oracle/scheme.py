@@ -136,19 +136,15 @@ def crt_centered(residues, primes):
     return res
 
 
-def decrypt(p: Params, keys: KeyPair, ct, level: int):
-    """ct: (2, level, N).  Returns the centred integer plaintext as a list of Python ints."""
-    d = np.zeros((level, p.N), dtype=np.int64)
-    for j in range(level):
-        q = p.primes[j]
-        d[j] = (ct[0, j] + negacyclic_mul(ct[1, j], keys.s % q, q, p.psi(j))) % q
-    return crt_centered(d, p.primes[:level])
-
-
 def decrypt_residues(p: Params, keys: KeyPair, ct, level: int):
-    """d_j = c0_j + c1_j * s mod q_j as (level, N) int64 (before the CRT lift)."""
+    """Dec before the lift: d_j = c0_j + c1_j * s mod q_j as (level, N) int64.  ct: (2, level, N)."""
     d = np.zeros((level, p.N), dtype=np.int64)
     for j in range(level):
         q = p.primes[j]
         d[j] = (ct[0, j] + negacyclic_mul(ct[1, j], keys.s % q, q, p.psi(j))) % q
     return d
+
+
+def decrypt(p: Params, keys: KeyPair, ct, level: int):
+    """ct: (2, level, N).  Returns the centred integer plaintext as a list of Python ints."""
+    return crt_centered(decrypt_residues(p, keys, ct, level), p.primes[:level])

@@ -130,6 +130,27 @@ def decode_wrong_scale(v, log2_n, scale_bits):  # divides by 2*Delta
     return _GOOD["decode_def"](v, log2_n, scale_bits) / 2
 
 
+def encode_fixed_scale(z, log2_n, scale_bits):  # ignores the scaling bits: always 2^30
+    return _GOOD["encode_def"](z, log2_n, 30)
+
+
+def decode_fft_fixed_scale(v, log2_n, scale_bits):      # the fast decoder divides by 2^30 whatever the scale
+    return _GOOD["decode_fft"](v, log2_n, 30)
+
+
+def decrypt_residues_without_c0(p, keys, ct, level):    # d = c1 * s
+    zero = np.zeros_like(np.asarray(ct, dtype=np.int64))
+    zero[1] = np.asarray(ct, dtype=np.int64)[1]
+    return _GOOD["decrypt_residues"](p, keys, zero, level)
+
+
+def decrypt_residues_minus(p, keys, ct, level):         # d = c0 - c1 * s
+    ct = np.asarray(ct, dtype=np.int64).copy()
+    for j in range(level):
+        ct[1, j] = (-ct[1, j]) % p.primes[j]
+    return _GOOD["decrypt_residues"](p, keys, ct, level)
+
+
 def plain_fedavg_float32(ws, alpha):            # accumulates in float32
     acc = np.zeros(np.asarray(ws[0]).shape, dtype=np.float32)
     for a, w in zip(alpha, ws):
@@ -156,6 +177,7 @@ def select_smallest(sens, ratio):               # keeps the least sensitive para
 
 _GOOD = {"keygen": scheme.keygen, "crt_centered": scheme.crt_centered, "intt": ring.intt, "ntt": ring.ntt,
          "sample_cbd": philox.sample_cbd, "encode_def": encoder.encode_def, "decode_def": encoder.decode_def,
+         "decode_fft": encoder.decode_fft, "decrypt_residues": scheme.decrypt_residues,
          "select_top": select.select_top}
 
 
@@ -181,10 +203,14 @@ CASES = [
     ("ternary sampler reads the block backwards", philox, "sample_ternary", ternary_wrong_word, pins_philox.test_samplers_follow_their_word_layout),
     ("binomial sampler uses eta + 1 bits", philox, "sample_cbd", cbd_wrong_mask, pins_philox.test_samplers_follow_their_word_layout),
     ("uniform sampler reduces 32 bits", philox, "sample_uniform", uniform_low_word_only, pins_philox.test_samplers_follow_their_word_layout),
-    ("encoder with sine", encoder, "encode_def", encode_sine, lambda: pins_encoder.test_encode_closed_forms(4)),
-    ("encoder without the factor 2", encoder, "encode_def", encode_missing_factor_two, lambda: pins_encoder.test_encode_closed_forms(4)),
-    ("fast encoder with slots at natural bins", encoder, "encode_fft", encode_fft_natural_slots, lambda: pins_encoder.test_encode_closed_forms(4)),
-    ("decoder divides by 2*Delta", encoder, "decode_def", decode_wrong_scale, lambda: pins_encoder.test_decode_is_evaluation_at_the_rotation_group(4)),
+    ("encoder with sine", encoder, "encode_def", encode_sine, lambda: pins_encoder.test_encode_closed_forms(4, 30)),
+    ("encoder without the factor 2", encoder, "encode_def", encode_missing_factor_two, lambda: pins_encoder.test_encode_closed_forms(4, 30)),
+    ("fast encoder with slots at natural bins", encoder, "encode_fft", encode_fft_natural_slots, lambda: pins_encoder.test_encode_closed_forms(4, 30)),
+    ("decoder divides by 2*Delta", encoder, "decode_def", decode_wrong_scale, lambda: pins_encoder.test_decode_is_evaluation_at_the_rotation_group(4, 30)),
+    ("encoder ignores the scaling bits", encoder, "encode_def", encode_fixed_scale, lambda: pins_encoder.test_encode_closed_forms(4, 20)),
+    ("fast decoder ignores the scaling bits", encoder, "decode_fft", decode_fft_fixed_scale, lambda: pins_encoder.test_decode_is_evaluation_at_the_rotation_group(4, 20)),
+    ("decryption drops c0", scheme, "decrypt_residues", decrypt_residues_without_c0, _with_ctx(pins_scheme.test_decrypt_residues_per_limb)),
+    ("decryption subtracts c1*s", scheme, "decrypt_residues", decrypt_residues_minus, _with_ctx(pins_scheme.test_decrypt_residues_per_limb)),
     ("plain FedAvg in float32", fedavg, "plain_fedavg", plain_fedavg_float32, pins_fedavg.test_plain_fedavg_against_exact_rationals),
     ("plain FedAvg ignores the weights", fedavg, "plain_fedavg", plain_fedavg_unweighted, pins_fedavg.test_plain_fedavg_against_exact_rationals),
     ("selection ties to the higher index", select, "select_top", select_ties_to_higher_index, pins_select.test_select_matches_the_counting_definition),

@@ -215,3 +215,69 @@ def test_client_weighted_plain_part_exact_cases():
     assert np.array_equal(fedavg.plain_weighted(w, 1.0), w)
     assert np.array_equal(fedavg.plain_weighted(w, 0.5), (w.astype(np.float64) / 2).astype(np.float32))
     assert np.array_equal(fedavg.plain_sum([w, w]), (2 * w.astype(np.float64)).astype(np.float32))
+
+
+def test_decrypt_residues_per_limb(ctx):
+    """The residues before the lift: in every limb d_j - m is the fresh noise built from the sampled pieces (reduced
+    mod q_j), at the full level and with the last limb dropped; lifting them gives what decrypt returns."""
+    p, keys = ctx
+    seed, client, ct_index = 777, 1, 9
+    rs = np.random.default_rng(5)
+    m = rs.integers(-(1 << 28), 1 << 28, p.N)
+    ct = scheme.encrypt(p, keys, m, seed, client, ct_index)
+    u = rng.sample_ternary(seed, p.N, ct_index, client, rng.TAG_U)
+    e0 = rng.sample_cbd(seed, p.N, p.cbd_eta, ct_index, client, rng.TAG_E0)
+    e1 = rng.sample_cbd(seed, p.N, p.cbd_eta, ct_index, client, rng.TAG_E1)
+    noise = _signed_negacyclic(keys.e, u) + e0 + _signed_negacyclic(e1, keys.s)
+    for level in (p.n_limbs, p.n_limbs - 1, 1):
+        d = scheme.decrypt_residues(p, keys, ct[:, :level], level)
+        assert d.shape == (level, p.N) and d.min() >= 0
+        for j in range(level):
+            q = p.primes[j]
+            assert d[j].max() < q
+            assert np.array_equal(_centered(d[j] - m, q), noise)
+        assert scheme.crt_centered(d, p.primes[:level]) == scheme.decrypt(p, keys, ct[:, :level], level)
+        if level > 1:      # one limb alone cannot hold m + noise centred (|m| reaches 2^28 < q/2: it can), more limbs agree
+            assert scheme.decrypt(p, keys, ct[:, :level], level) == [int(x) for x in (m + noise)]
+
+
+def test_reusing_a_seed_leaks_the_update_difference(ctx):
+    """Why (seed, client) must be fresh for every round: with the same randomness the two ciphertexts share c1, and
+    c0 - c0' is the difference of the plaintexts, readable without any key."""
+    p, keys = ctx
+    rs = np.random.default_rng(6)
+    m1 = rs.integers(-(1 << 28), 1 << 28, p.N)
+    m2 = rs.integers(-(1 << 28), 1 << 28, p.N)
+    a = scheme.encrypt(p, keys, m1, 99, 3, 0)
+    b = scheme.encrypt(p, keys, m2, 99, 3, 0)
+    assert np.array_equal(a[1], b[1])
+    for j, q in enumerate(p.primes):
+        assert np.array_equal(_centered(a[0, j] - b[0, j], q), m1 - m2)
+    c = scheme.encrypt(p, keys, m2, 100, 3, 0)          # a fresh seed: nothing in common
+    assert not np.array_equal(a[1], c[1])
+    assert not np.array_equal(_centered(a[0, 0] - c[0, 0], p.primes[0]), m1 - m2)
+
+
+@pytest.mark.parametrize("log2_n,limbs,scale_bits", [(11, 3, 20), (13, 3, 20), (11, 3, 30)])
+def test_round_at_other_crypto_parameters(log2_n, limbs, scale_bits):
+    """The crypto-parameter sweep's settings (packing batch 1024 and 4096, 20 scaling bits): the whole oracle round
+    against float64 FedAvg under the noise model, whose sigma scales with 1 / Delta."""
+    p = Params(log2_n, limbs, scale_bits=scale_bits)
+    keys = scheme.keygen(p, 4321)
+    rs = np.random.default_rng(14)
+    K = 3
+    P = 2 * p.n_slots + 321
+    ws = [rs.normal(0, 0.05, P).astype(np.float32) for _ in range(K)]
+    alpha = np.array([0.5, 0.3, 0.2])
+    runs = [(7, p.n_slots + 11), (p.n_slots + 100, p.n_slots // 2)]
+    out = fedavg.secure_round(p, keys, ws, alpha, runs, seed=5)
+    out_def = fedavg.secure_round(p, keys, ws, alpha, runs, seed=5, fast=False) if log2_n <= 11 else None
+    ref = fedavg.fedavg_float64(ws, alpha)
+    enc_idx, plain_idx = fedavg.mask_indices(P, runs)
+    assert np.array_equal(out[plain_idx], ref[plain_idx].astype(np.float32))
+    err = out[enc_idx].astype(np.float64) - ref[enc_idx]
+    sigma = fedavg.noise_sigma(p, alpha)
+    assert sigma == pytest.approx(fedavg.noise_sigma(Params(log2_n, limbs), alpha) * 2.0 ** (30 - scale_bits))
+    assert 0.7 * sigma < np.sqrt((err ** 2).mean()) < 1.4 * sigma and np.abs(err).max() < 16 * sigma
+    if out_def is not None:     # the definition-based encoder / decoder give the same round up to the encoder's +-1
+        assert np.abs(out_def.astype(np.float64) - out.astype(np.float64)).max() <= 4.0 * p.N ** 0.5 / p.delta + 1e-7
