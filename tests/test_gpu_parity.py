@@ -158,7 +158,8 @@ def test_encrypt_given_plaintext(he, log2_n, limbs, eta):
         assert np.array_equal(ct[c], ref), (c,)
 
 
-@pytest.mark.parametrize("log2_n,limbs,K", [(4, 3, 3), (10, 2, 5), (13, 3, 3), (14, 4, 8), (10, 3, 1), (10, 3, 37), (10, 4, 70), (10, 3, 200)])
+@pytest.mark.parametrize("log2_n,limbs,K", [(4, 3, 3), (10, 2, 5), (13, 3, 3), (14, 4, 8), (10, 3, 1), (10, 3, 37), (10, 4, 70), (10, 3, 200),
+                                            (10, 5, 70), (10, 8, 70), (13, 5, 9), (14, 8, 3), (10, 6, 130)])
 def test_aggregate_and_streaming(he, log2_n, limbs, K):
     ctx, _, p, _ = _setup(he, log2_n, limbs)
     rs = np.random.default_rng(3)
@@ -178,7 +179,8 @@ def test_aggregate_and_streaming(he, log2_n, limbs, K):
     # streaming form, uneven chunks, same client order -> identical bytes
     acc_ct, acc_pl = he.he_aggregate_begin(ctx, n_ct, n_plain)
     cut = max(1, K // 3)
-    for lo, hi in [(0, cut), (cut, K)]:
+    cut2 = min(K, cut + max(1, K // 7))
+    for lo, hi in [(0, cut), (cut, cut2), (cut2, K)]:
         if hi > lo:
             he.he_aggregate_add(ctx, alpha[lo:hi], d_cts[lo:hi], d_pl[lo:hi], acc_ct, acc_pl)
     ct_s, pl_s = he.he_aggregate_finalize(ctx, acc_ct, acc_pl)
@@ -227,6 +229,35 @@ def test_decrypt_residues_and_decode(he, log2_n, limbs):
             ref = oenc.decode_fft(np.array([float(x) for x in v]), log2_n, 30)
             scale = max(1.0, np.abs(ref).max())
             assert np.abs(z[c] - ref).max() <= 1e-6 * scale if d is d_rand else np.abs(z[c] - ref).max() <= 1e-9
+
+
+@pytest.mark.parametrize("log2_n,limbs", [(10, 3), (13, 3), (14, 4), (12, 5)])
+def test_decrypt_merge_at_every_level(he, log2_n, limbs):
+    """he_decrypt_merge_level at levels 1 .. L (a fresh ciphertext cut down to its first `level` limbs still decrypts to
+    m + noise as long as that fits q_0 / 2): decoded and scattered values against the oracle's at the same level."""
+    ctx, keys, p, okeys = _setup(he, log2_n, limbs)
+    n = p.n_slots
+    P = n + 37
+    runs = [(3, n // 2), (n // 2 + 20, n // 2 + 5)]          # two ciphertexts, the second nearly empty
+    mask = he.he_mask_create(ctx, P, [r[0] for r in runs], [r[1] for r in runs])
+    enc_idx, plain_idx = ofed.mask_indices(P, runs)
+    rs = np.random.default_rng(30 + limbs)
+    w = rs.normal(0, 0.05, P).astype(np.float32)
+    ct, pl = he.he_encrypt_masked(ctx, keys, mask, SEED + 5, 2, _dev(w))
+    ct_h = _np(ct).astype(np.int64)
+    for level in range(1, limbs + 1):
+        cut = ct[:, :, :level].contiguous()
+        out = _np(he.he_decrypt_merge_level(ctx, keys, mask, level, cut, pl))
+        assert np.array_equal(out[plain_idx], w[plain_idx])
+        for c in range(mask.n_ct):
+            z = ofed.decode_ct_level(p, okeys, ct_h[c][:, :level], level)
+            sel = enc_idx[c * n:(c + 1) * n]
+            assert np.abs(out[sel].astype(np.float64) - z[:len(sel)].astype(np.float32).astype(np.float64)).max() <= 1e-6, (level, c)
+        assert np.abs(out[enc_idx] - w[enc_idx]).max() < 16 * ofed.noise_sigma(p, [1.0])
+    for bad in (0, limbs + 1):
+        with pytest.raises(he.HeError):
+            he.he_decrypt_merge_level(ctx, keys, mask, bad, torch.zeros((mask.n_ct, 2, bad, ctx.N), dtype=torch.int32, device="cuda"), pl)
+    mask.close()
 
 
 def _gpu_round(he, ctx, keys, mask, ws, alpha, seed):
