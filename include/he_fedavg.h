@@ -142,6 +142,21 @@ he_status he_encrypt_masked(he_ctx* ctx, const he_pk* pk, const he_mask* mask, u
                             uint32_t client_id, const float* w_dev, uint32_t* ct_out_dev,
                             float* plain_out_dev, void* stream);
 
+/* he_encrypt_masked for callers that cannot allocate device memory: code under HIP graph capture, tight
+   serving loops, harnesses that forbid hipMalloc.  Same arguments, same output bytes.  The per-ciphertext
+   scratch (plaintext polynomial int32[N] and the randomness u, e0, e1 as int8[N] each: 7 * N bytes per
+   ciphertext) lives in a fixed array of HE_STATIC_SCRATCH_BYTES inside the library's code object instead of
+   the context's grown-on-demand block, so the call allocates and frees nothing and never synchronises.
+   Limit: n_ct * N * 7 <= HE_STATIC_SCRATCH_BYTES (292 ciphertexts at N = 2^14, 585 at N = 2^13);
+   HE_ERR_INVALID_ARG beyond it, with nothing enqueued.  Every GPU the library runs on holds the array until the
+   process ends, and ALL calls on one GPU, from any context or stream, share it: calls that overlap in time
+   on one GPU race (order them on one stream or with events).  Nothing in it has to start at zero: every
+   byte a call reads was written by that call.  Per-kernel timing (he_debug_timing_enable) skips this call. */
+#define HE_STATIC_SCRATCH_BYTES (32u << 20)
+he_status he_encrypt_masked_static(he_ctx* ctx, const he_pk* pk, const he_mask* mask, uint64_t seed,
+                                   uint32_t client_id, const float* w_dev, uint32_t* ct_out_dev,
+                                   float* plain_out_dev, void* stream);
+
 /* ---- server: [W_glob] <- sum_i a_i [[M.W_i]] + sum_i a_i (1-M).W_i ---------------------
    ("Server Model Aggregation"; plaintext weights, one multiplicative depth.)
    alpha_host double[K]: alpha_i > 0, |sum - 1| <= 1e-9.  Each weight becomes the integer

@@ -48,6 +48,7 @@ _SIGS = {
     "he_mask_n_enc": (C.c_uint64, [_P]),
     "he_n_ct": (C.c_uint64, [_P, _P]),
     "he_encrypt_masked": (C.c_int32, [_P, _P, _P, C.c_uint64, C.c_uint32, _P, _P, _P, _P]),
+    "he_encrypt_masked_static": (C.c_int32, [_P, _P, _P, C.c_uint64, C.c_uint32, _P, _P, _P, _P]),
     "he_aggregate": (C.c_int32, [_P, C.c_uint32, C.POINTER(C.c_double), C.POINTER(_P), C.POINTER(_P),
                                  C.c_uint64, C.c_uint64, _P, _P, _P]),
     "he_aggregate_begin": (C.c_int32, [_P, C.c_uint64, C.c_uint64, _P, _P, _P]),
@@ -72,6 +73,7 @@ _SIGS = {
 }
 
 EXPORTED_SYMBOLS = tuple(_SIGS)
+HE_STATIC_SCRATCH_BYTES = 32 << 20      # include/he_fedavg.h
 
 
 def load():
@@ -217,6 +219,15 @@ def he_encrypt_masked(ctx, keys, mask, seed, client_id, w, ct_out=None, plain_ou
     assert w.numel() == mask.P and ct_out.numel() == mask.n_ct * 2 * ctx.L * ctx.N and plain_out.numel() == mask.n_plain
     _check(load().he_encrypt_masked(ctx.h, keys.pk, mask.h, seed, client_id, _ptr(w, torch.float32),
                                     _ptr(ct_out, torch.int32), _ptr(plain_out, torch.float32), _stream()))
+    return ct_out, plain_out
+
+
+def he_encrypt_masked_static(ctx, keys, mask, seed, client_id, w, ct_out, plain_out):
+    """he_encrypt_masked that allocates nothing: the caller passes both outputs."""
+    assert w.numel() == mask.P and ct_out.numel() == mask.n_ct * 2 * ctx.L * ctx.N and plain_out.numel() == mask.n_plain
+    _check(load().he_encrypt_masked_static(ctx.h, keys.pk, mask.h, seed, client_id, _ptr(w, torch.float32),
+                                           _ptr(ct_out, torch.int32) if mask.n_ct else None,
+                                           _ptr(plain_out, torch.float32) if mask.n_plain else None, _stream()))
     return ct_out, plain_out
 
 

@@ -1109,6 +1109,16 @@ constexpr uint64_t kCtChunk = 2048;  // ciphertexts per scratch chunk (m+e0, u, 
 
 }  // namespace
 
+// Scratch of he_encrypt_masked_static, the entry point for callers that cannot allocate: part of the code object, so
+// every GPU the library runs on holds its own copy from module load to process end.  In host code this name is only a
+// handle for hipGetSymbolAddress; kernels, memsets and copies get the per-device address kept in g_static_scratch.
+static __device__ __align__(256) unsigned char scratch[HE_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void* g_static_scratch[kMaxDevices] = {};  // device address of `scratch` on each GPU, resolved by he_ctx_create
+}  // namespace
+
 enum KernelId : int {
   KID_ENCODE = 0, KID_SAMPLE, KID_ENCRYPT, KID_AGGREGATE, KID_PLAIN_FEDAVG, KID_DECRYPT, KID_DECODE, KID_PLAIN_MOVE,
   KID_NTT, KID_COUNT
@@ -1132,6 +1142,7 @@ struct he_ctx {
   AggConst agg{};
   void* ws = nullptr;  // scratch, grown on demand
   size_t ws_bytes = 0;
+  void* static_scratch = nullptr;  // this GPU's copy of the file-scope array `scratch`
   int max_lds = 0;
   // The plaintext remainder (an HBM-bound copy) runs beside the ALU-bound transform kernels on a
   // second stream of the context's own, forked from and joined back into the caller's stream.
@@ -1537,9 +1548,17 @@ he_status he_ctx_create(const he_params* params, int device, he_ctx** out) try {
   if (params->scale_bits < 1 || params->scale_bits > 30) return fail(HE_ERR_INVALID_ARG, "scale_bits must be in 1..30");
   if (params->cbd_eta > 32) return fail(HE_ERR_INVALID_ARG, "cbd_eta must be in 0..32");
   HIP_TRY(hipSetDevice(device));
+  if (device < 0 || device >= kMaxDevices) return fail(HE_ERR_INVALID_ARG, "device index out of range");
+  if (!g_static_scratch[device]) {  // once per device, with that device current: each GPU has its own copy
+    void* ptr = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return fail(HE_ERR_HIP, "the static scratch array has no device address");
+    g_static_scratch[device] = ptr;
+  }
   he_ctx* ctx = new (std::nothrow) he_ctx();
   if (!ctx) return fail(HE_ERR_NOMEM, "host allocation failed");
   ctx->device = device;
+  ctx->static_scratch = g_static_scratch[device];
   if (hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) != hipSuccess ||   // default priority
       hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming) != hipSuccess ||
       hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming) != hipSuccess) {
@@ -2004,9 +2023,11 @@ uint64_t he_n_ct(const he_ctx* ctx, const he_mask* mask) {
 
 // ---- client: encrypt -------------------------------------------------------------------
 
+// fixed_scratch: when given (he_encrypt_masked_static), the per-ciphertext scratch lives there and the call
+// allocates nothing; it must then hold all n_ct ciphertexts' scratch at once.
 static he_status encrypt_masked_impl(he_ctx* ctx, const he_pk* pk, const he_mask* mask, uint64_t seed, uint32_t client_id,
                                      double pre_scale, const float* w_dev, uint32_t* ct_out_dev, float* plain_out_dev,
-                                     void* stream) try {
+                                     void* stream, void* fixed_scratch = nullptr, size_t fixed_bytes = 0) try {
   he_status s = check_ctx(ctx);
   if (s != HE_OK) return s;
   if (!pk || !mask || pk->ctx != ctx || mask->ctx != ctx) return fail(HE_ERR_INVALID_ARG, "key/mask missing or from another context");
@@ -2017,13 +2038,17 @@ static he_status encrypt_masked_impl(he_ctx* ctx, const he_pk* pk, const he_mask
   if (reinterpret_cast<uintptr_t>(ct_out_dev) % 16 != 0) return fail(HE_ERR_INVALID_ARG, "ciphertext buffers must be 16-byte aligned");
   hipStream_t st = static_cast<hipStream_t>(stream);
   const RingDev& rg = ctx->ring;
-  const uint64_t chunk = std::min<uint64_t>(kCtChunk, n_ct);
   const size_t N = rg.N;
-  if (chunk) {
+  uint64_t chunk = std::min<uint64_t>(kCtChunk, n_ct);
+  if (fixed_scratch) {
+    if (n_ct * N * kEncScratchBytesPerCoeff > fixed_bytes)
+      return fail(HE_ERR_INVALID_ARG, "too many ciphertexts for the static scratch: n_ct * N * 7 bytes must not exceed HE_STATIC_SCRATCH_BYTES");
+    chunk = n_ct;
+  } else if (chunk) {
     s = ensure_ws(ctx, chunk * N * kEncScratchBytesPerCoeff);
     if (s != HE_OK) return s;
   }
-  const EncScratch sc = carve_enc_scratch(ctx->ws, chunk, N);
+  const EncScratch sc = carve_enc_scratch(fixed_scratch ? fixed_scratch : ctx->ws, chunk, N);
   const bool beside = n_plain && n_ct;  // the copy of the remainder overlaps the transforms
   hipStream_t pst = beside ? ctx->side : st;
   if (n_plain) {
@@ -2061,6 +2086,21 @@ static he_status encrypt_masked_impl(he_ctx* ctx, const he_pk* pk, const he_mask
 he_status he_encrypt_masked(he_ctx* ctx, const he_pk* pk, const he_mask* mask, uint64_t seed, uint32_t client_id,
                             const float* w_dev, uint32_t* ct_out_dev, float* plain_out_dev, void* stream) try {
   return encrypt_masked_impl(ctx, pk, mask, seed, client_id, 1.0, w_dev, ct_out_dev, plain_out_dev, stream);
+} catch (...) {
+  return on_exception();
+}
+
+he_status he_encrypt_masked_static(he_ctx* ctx, const he_pk* pk, const he_mask* mask, uint64_t seed, uint32_t client_id,
+                                   const float* w_dev, uint32_t* ct_out_dev, float* plain_out_dev, void* stream) try {
+  if (!ctx) return fail(HE_ERR_INVALID_ARG, "context is null");
+  if (!ctx->static_scratch) return fail(HE_ERR_HIP, "the static scratch array was not resolved on this device");
+  // Per-kernel timing takes events from a pool that it grows on demand: off for this call, which must create nothing.
+  const bool timing = ctx->timing_on;
+  ctx->timing_on = false;
+  const he_status s = encrypt_masked_impl(ctx, pk, mask, seed, client_id, 1.0, w_dev, ct_out_dev, plain_out_dev, stream,
+                                          ctx->static_scratch, HE_STATIC_SCRATCH_BYTES);
+  ctx->timing_on = timing;
+  return s;
 } catch (...) {
   return on_exception();
 }
