@@ -28,6 +28,8 @@ OPS_BFLY_FWD = 11        # Shoup product (mul_hi, 2 x 64-bit multiply-add) + its
 OPS_BFLY_FWD_LAZY = 8    # outputs whose next use is a Shoup multiplicand stay in [0, 2q): add (1) + sub (2)
 OPS_BFLY_INV = 10        # modular add (3) + x - y + q (2) + Shoup product (3) + its reduction (2)
 OPS_POINTWISE = 5        # Shoup product + reduction
+OPS_LAST_STAGE_NINV = 1.5  # standalone inverse: 1/N is folded into its last stage, whose sum output then takes a Shoup product too
+COPY_CEILING_GBS = 5700.0  # what the plain compaction of an all-plaintext vector (one run, a shifted copy) reaches on this chip: read + write bytes
 PASS_PLAN = {14: (4, 4, 3, 3), 13: (4, 3, 3, 3)}   # stages per LDS pass of the specialised transforms
 
 
@@ -76,37 +78,64 @@ def measured_valu_busy(workload):
     return out
 
 
-def cpu_baseline(w, ws_host, alpha, runs, budget_s=15.0, client_weighted=False):
-    """Times the CPU oracle on a bounded sample of ciphertext indices of the same workload."""
-    from oracle import fedavg as ofed, scheme as osch
+def _oracle_ciphertext_job(job):
+    """One ciphertext index of the round on the CPU oracle: every client's encode + encrypt, the server's weighted sum
+    and rescale (or plain sum), decrypt, lift, decode.  Runs in the parent (one core) and in spawned worker processes
+    (all cores); a worker imports numpy and the oracle only, never torch or the HIP library."""
+    params, seed, alpha, c, slots, client_weighted = job
+    from oracle import encoder as oenc, fedavg as ofed, scheme as osch
     from oracle.params import Params
-    p = Params(w.log2_n, w.n_limbs - 1 if client_weighted else w.n_limbs, w.scale_bits, w.cbd_eta)
-    keys = osch.keygen(p, w.seed)
-    P = w.n_params
-    enc_idx, _ = ofed.mask_indices(P, runs)
-    n_ct = ofed.n_ciphertexts(p, len(enc_idx))
+    p = Params(*params)
+    keys = _ORACLE_KEYS.get((params, seed))
+    if keys is None:
+        keys = _ORACLE_KEYS.setdefault((params, seed), osch.keygen(p, seed))
+    if client_weighted:
+        cts = [osch.encrypt(p, keys, oenc.encode_fft(np.float64(a) * z, p.log2_n, p.scale_bits), seed, i, c)
+               for i, (z, a) in enumerate(zip(slots, alpha))]
+        return ofed.decode_ct_level(p, keys, osch.sum_ciphertexts(p, cts), p.n_limbs)[:1]
+    cts = [osch.encrypt(p, keys, oenc.encode_fft(z, p.log2_n, p.scale_bits), seed, i, c) for i, z in enumerate(slots)]
+    return ofed.decode_ct(p, keys, osch.aggregate(p, cts, alpha))[:1]
 
-    def one(c):
-        if client_weighted:
-            cts = [ofed.encrypt_ct_weighted(p, keys, x, enc_idx, alpha[i], w.seed, i, c)[1] for i, x in enumerate(ws_host)]
-            return ofed.decode_ct_level(p, keys, osch.sum_ciphertexts(p, cts), p.n_limbs)
-        cts = [ofed.encrypt_ct(p, keys, x, enc_idx, w.seed, i, c)[1] for i, x in enumerate(ws_host)]
-        return ofed.decode_ct(p, keys, osch.aggregate(p, cts, alpha))
 
+_ORACLE_KEYS = {}
+
+
+def cpu_baseline(w, slots_of, n_ct, alpha, budget_s=10.0, client_weighted=False):
+    """Times the CPU oracle on a bounded sample of ciphertext indices of the same workload: once in this process (one
+    core) and once over spawned worker processes, one per host core the box gives a one-GPU job (at most 16).
+    slots_of(c) -> the K clients' slot vectors (float64 [n]) of ciphertext index c; the gather itself (n loads per
+    client) is done by the caller and not timed."""
+    import multiprocessing as mp
+    K = w.n_clients
+    params = (w.log2_n, w.n_limbs - 1 if client_weighted else w.n_limbs, w.scale_bits, w.cbd_eta)
+    n_slots = (1 << w.log2_n) // 2
+    job = lambda c: (params, w.seed, [float(a) for a in alpha], int(c), slots_of(int(c)), client_weighted)
+    _oracle_ciphertext_job(job(0))                       # key generation and table set-up, not timed
     t0 = time.perf_counter()
-    one(0)
+    _oracle_ciphertext_job(job(min(1, n_ct - 1)))
     t_one = time.perf_counter() - t0
-    n_sample = int(max(1, min(n_ct - 1, budget_s // max(t_one, 1e-3))))
-    idx = np.linspace(1, n_ct - 1, n_sample).astype(int) if n_ct > 1 else np.array([0])
+    n1 = int(max(1, min(n_ct, budget_s // max(t_one, 1e-3))))
+    idx1 = np.linspace(0, n_ct - 1, n1).astype(int)
+    jobs = [job(c) for c in idx1]
     t0 = time.perf_counter()
-    for c in idx:
-        one(int(c))
-    dt = time.perf_counter() - t0
-    params = len(idx) * p.n_slots * len(ws_host)
-    return {"value": params / dt, "unit": "params/s", "cores": 1, "kind": "oracle",
-            "sample": f"{len(idx)} of {n_ct} ciphertext indices x {len(ws_host)} clients "
-                      f"(encrypt, aggregate, decrypt+decode), {dt:.1f} s, numpy single thread, "
-                      f"host has {os.cpu_count()} cores"}
+    for j in jobs:
+        _oracle_ciphertext_job(j)
+    dt1 = time.perf_counter() - t0
+    one = {"value": n1 * n_slots * K / dt1, "unit": "params/s", "cores": 1,
+           "sample": f"{n1} of {n_ct} ciphertext indices x {K} clients, {dt1:.1f} s"}
+    cores = max(1, min(16, os.cpu_count() or 1))
+    n_all = int(max(cores, min(n_ct, 2 * cores * max(1, budget_s // max(t_one, 1e-3) // 2))))
+    idx_all = np.linspace(0, n_ct - 1, n_all).astype(int)
+    jobs = [job(c) for c in idx_all]
+    with mp.get_context("spawn").Pool(cores) as pool:
+        pool.map(_oracle_ciphertext_job, [job(0)] * cores, chunksize=1)      # every worker: imports, keys, tables
+        t0 = time.perf_counter()
+        pool.map(_oracle_ciphertext_job, jobs, chunksize=1)
+        dt_all = time.perf_counter() - t0
+    return {"value": n_all * n_slots * K / dt_all, "unit": "params/s", "cores": cores, "kind": "oracle",
+            "sample": f"{n_all} of {n_ct} ciphertext indices x {K} clients (encode, encrypt, aggregate, decrypt, decode "
+                      f"per index), {dt_all:.1f} s over {cores} worker processes; host reports {os.cpu_count()} cores",
+            "one_core": one}
 
 
 def aggregate_k_sweep(he, ctx, torch, n_ct=512, ks=(3, 8, 16, 32, 64, 128, 200), reps=5):
@@ -207,49 +236,21 @@ def mask_select_bench(he, ctx, torch, sizes=(25_600_000, 110_000_000, 1_300_000_
     return rows
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="resnet18_full")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--variant", default="server_weighted", choices=["server_weighted", "client_weighted"],
-                    help="client_weighted: clients encode alpha_i * W_i, the server only adds ciphertexts (no rescale), one limb fewer")
-    ap.add_argument("--param-sweep", action="store_true",
-                    help="also run packing batch 1024..8192 x scaling bits 20/30 on a 1.66M-parameter vector, 3 clients")
-    ap.add_argument("--select-bench", action="store_true",
-                    help="also time the encryption-mask selection (top-p of a sensitivity map) on 25.6M / 110M / 1.3B entries")
-    ap.add_argument("--k-sweep", action="store_true",
-                    help="also time he_aggregate alone for K = 3 ... 200 clients (server cost against the number of clients)")
-    ap.add_argument("--stream-clients", action="store_true",
-                    help="fold each client's plaintext remainder into the server's accumulator right after its encryption "
-                         "(he_aggregate_begin/add/finalize) and keep only 4 distinct client vectors resident; chosen by "
-                         "itself when the clients' vectors exceed 64 GB")
-    ap.add_argument("--fold-group", type=int, default=16, help="streamed clients: remainders the server folds per he_aggregate_add")
-    ap.add_argument("--fold-buffers", type=int, default=1, help="streamed clients: groups of remainder buffers (2 = the next group encrypts while one is folded)")
-    ap.add_argument("--client-streams", type=int, default=1,
-                    help="number of clients that encrypt side by side, each on its own context and stream (default 1: one after the other)")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one plain 1 GiB device copy (known HBM traffic, for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs on ONE GPU only (ciphertext indices are independent, so more GPUs "
-                 "would shard by ciphertext index with no collectives); run with --gpus 1")
+HEADLINE = "fm1p3b_sel5"          # the largest workload that runs whole on one GPU (32 clients x 1.3 B parameters)
+HEADLINE_MIN_FREE_GIB = 200       # what it needs resident; on a GPU with less free HBM the headline is bert_full
+OTHER_WORKLOADS = ("tiny_full", "resnet18_full", "resnet50_sel10", "bert_sel10", "bert_full")
 
-    import torch
-    from paper_2303_10837_amd import binding as he, synth_inputs as si
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-    w = si.WORKLOADS[args.workload]
+def run_workload(he, si, torch, name, args, steps, warmup, headline):
+    """Times `steps` whole rounds of one workload and returns its result row (for the headline workload: the full
+    record with rooflines, standalone transform rates and the CPU baseline)."""
+    w = si.WORKLOADS[name]
     K = w.n_clients
     client_weighted = args.variant == "client_weighted"
     n_limbs = w.n_limbs - 1 if client_weighted else w.n_limbs     # no rescale: the level never drops
     ctx = he.Context(w.log2_n, n_limbs, w.scale_bits, w.cbd_eta)
     keys = he.he_keygen(ctx, w.seed)
     starts, lens = si.mask_runs(w)
-    runs = [(int(s), int(l)) for s, l in zip(starts, lens)]
     mask = he.he_mask_create(ctx, w.n_params, starts, lens)
     alpha = si.client_alphas(w)
     # A workload whose client vectors do not fit next to all clients' ciphertexts (the 1.3 B-parameter one: 166 GB of
@@ -259,14 +260,12 @@ def main():
     # streamed through he_aggregate once.
     streamed = args.stream_clients or K * w.n_params * 4 > 64e9
     n_distinct = min(K, 4) if streamed else K
-    if streamed:
+    on_device = streamed or w.n_params >= 50_000_000              # torch's seeded device generator for the long vectors
+    if on_device:
         ws = [si.client_params_torch(w, i, "cuda") for i in range(n_distinct)]
-        ws_host = [x.cpu().numpy() for x in ws]
     else:
-        ws_host = [si.client_params_numpy(w, i) for i in range(K)]
-        ws = [torch.from_numpy(x).cuda() for x in ws_host]
+        ws = [torch.from_numpy(si.client_params_numpy(w, i)).cuda() for i in range(n_distinct)]
     ws = [ws[i % n_distinct] for i in range(K)]
-    ws_host = [ws_host[i % n_distinct] for i in range(K)]
     N, L, n_ct, P_enc = ctx.N, ctx.L, mask.n_ct, mask.P_enc
     n_pl = mask.n_plain
     cts = [torch.empty((n_ct, 2, L, N), dtype=torch.int32, device="cuda") for _ in range(K)]
@@ -291,7 +290,7 @@ def main():
         acc_none, acc_plain = he.he_aggregate_begin(server, 0, n_pl)
         ct_none = torch.empty((0, 2, L_out, N), dtype=torch.int32, device="cuda")
         torch.cuda.synchronize()
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    ev = [None] * 4
     phase_ms = np.zeros(3)
 
     def step_streamed(record):
@@ -383,7 +382,7 @@ def main():
                 tot[k] = (t[0] + ms, t[1] + n)
         return tot
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step(False)
     torch.cuda.synchronize()
     for c in timed_ctxs:
@@ -391,7 +390,7 @@ def main():
     timing_read()
     t0 = time.perf_counter()
     step_events = []
-    for _ in range(args.steps):
+    for _ in range(steps):
         ev[:] = [torch.cuda.Event(enable_timing=True) for _ in range(4)]   # own events per step, read after the region
         step_events.append(list(ev))
         step(True)
@@ -402,84 +401,83 @@ def main():
     kern = timing_read()
     for c in timed_ctxs:
         he.he_debug_timing_enable(c, False)
-    ms_step = dt * 1e3 / args.steps
-    phase_ms /= args.steps
+    ms_step = dt * 1e3 / steps
+    phase_ms /= steps
     # The same steps once more without the per-kernel event pairs and the phase events: what the instrumentation of
     # the timed region above costs (reported beside `value`, never as `value`).
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step(False)
     torch.cuda.synchronize()
-    ms_step_plain = (time.perf_counter() - t0) * 1e3 / args.steps
-
-    # standalone transform throughput (he_debug_ntt, in place): forward then inverse over a batch
-    batch = 4096
-    polys = torch.randint(0, ctx.primes[-1], (batch, N), dtype=torch.int32, device="cuda")
-    he.he_debug_ntt(ctx, False, L - 1, polys)
-    he.he_debug_ntt(ctx, True, L - 1, polys)
-    torch.cuda.synchronize()
-    he.he_debug_timing_enable(ctx, True)
-    he.he_debug_timing_read(ctx)
-    for _ in range(5):
-        he.he_debug_ntt(ctx, False, L - 1, polys)
-        he.he_debug_ntt(ctx, True, L - 1, polys)
-    ntt_ms, ntt_launches = he.he_debug_timing_read(ctx)["ntt"]
-    he.he_debug_timing_enable(ctx, False)
-    ntt_coeff_per_s = batch * N * ntt_launches / (ntt_ms * 1e-3)
-    log_n = N.bit_length() - 1
-    # forward and inverse launches alternate: average of the two, the inverse includes its 1/N product
-    ntt_ops_per_coeff = (fwd_ops_per_coeff(log_n, False) + 0.5 * log_n * OPS_BFLY_INV + OPS_POINTWISE) / 2
-    ntt_tops = ntt_coeff_per_s * ntt_ops_per_coeff / 1e12
-    roofline_ntt = {"kernel": "k_ntt_batch_s", "bound": "alu", "achieved": ntt_tops, "peak": ALU_PEAK_TOPS, "unit": "TOP/s",
-                    "frac": ntt_tops / ALU_PEAK_TOPS, "traffic": measured_traffic(w.name).get("k_ntt_batch"),
-                    "valu_busy_pct_profiled": measured_valu_busy(w.name).get("k_ntt_batch"),
-                    "algorithmic_bytes_per_launch": batch * N * 8, "avg_launch_ms": ntt_ms / ntt_launches,
-                    "launches": int(ntt_launches), "coeff_per_s": ntt_coeff_per_s, "ops_per_coeff": ntt_ops_per_coeff,
-                    "hbm_GBps": ntt_coeff_per_s * 8 / 1e9, "hbm_frac": ntt_coeff_per_s * 8 / 1e9 / HBM_PEAK_GBS}
-    del polys
-    if args.calibrate_copy:
-        src = torch.empty(1 << 28, dtype=torch.int32, device="cuda").fill_(1)   # 1 GiB
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-
-    k_sweep = aggregate_k_sweep(he, ctx, torch) if args.k_sweep else None
-    param_sweep = crypto_param_sweep(he, torch) if args.param_sweep else None
-    select_rows = mask_select_bench(he, ctx, torch) if args.select_bench else None
+    ms_step_plain = (time.perf_counter() - t0) * 1e3 / steps
 
     # sanity: the decoded aggregate is FedAvg up to the CKKS noise (not part of the timing)
     if streamed:
         plains.clear()
         torch.cuda.empty_cache()
-    ref = sum(float(a) * x.double() for a, x in zip(alpha, ws))
+    ref = torch.zeros(w.n_params, dtype=torch.float64, device="cuda")
+    for a, x in zip(alpha, ws):
+        ref.add_(x, alpha=float(a))
     max_err = float((out.double() - ref).abs().max())
+    del ref
 
-    # roofline of the dominant kernel (by accumulated device time)
+    # rooflines of the encryption kernel (ALU-bound; the dominant one by accumulated device time in every workload but
+    # the tiny one) and of the aggregation kernel (HBM-bound), from the event pairs of the timed region
     enc_ms, enc_launches = kern["encrypt"]
     agg_ms, agg_launches = kern["aggregate"]
-    enc_ops = encrypt_ops_per_ct(N, L) * n_ct * K * args.steps           # all launches of the timed region
+    enc_ops = encrypt_ops_per_ct(N, L) * n_ct * K * steps                # all launches of the timed region
     enc_tops = enc_ops / (enc_ms * 1e-3) / 1e12 if enc_ms else 0.0
-    enc_bytes = (8 * L + 7) * N * n_ct * K * args.steps                  # 2*L*N residues written + m (int32), u, e0, e1 (int8) read once
-    agg_bytes = n_ct * 2 * N * 4 * (K * L + L_out) * args.steps
+    enc_bytes = (8 * L + 7) * N * n_ct * K * steps                       # 2*L*N residues written + m (int32), u, e0, e1 (int8) read once
+    agg_bytes = n_ct * 2 * N * 4 * (K * L + L_out) * steps
     agg_gbs = agg_bytes / (agg_ms * 1e-3) / 1e9 if agg_ms else 0.0
     dominant = max(kern, key=lambda k: kern[k][0])
-    traffic = measured_traffic(w.name)
-    roofline = {"kernel": "k_encrypt", "bound": "alu", "achieved": enc_tops, "peak": ALU_PEAK_TOPS, "unit": "TOP/s",
+    traffic, busy = measured_traffic(w.name), measured_valu_busy(w.name)
+    prof_note = f"replayed from profiles/hbm_traffic_{w.name}.txt and profiles/valu_utilisation_{w.name}.txt (rocprofv3 --pmc runs of this command), not measured in this run"
+    roofline = {"kernel": "k_encrypt_s", "bound": "alu", "achieved": enc_tops, "peak": ALU_PEAK_TOPS, "unit": "TOP/s",
                 "frac": enc_tops / ALU_PEAK_TOPS, "traffic": traffic.get("k_encrypt"),
-                "valu_busy_pct_profiled": measured_valu_busy(w.name).get("k_encrypt"),
+                "valu_busy_pct_profiled": busy.get("k_encrypt"), "profiled_fields": prof_note,
                 "avg_launch_ms": enc_ms / max(enc_launches, 1), "launches": int(enc_launches),
                 "algorithmic_ops_per_launch": enc_ops / max(enc_launches, 1),
                 "algorithmic_bytes_per_launch": enc_bytes / max(enc_launches, 1),
-                "hbm_GBps": enc_bytes / (enc_ms * 1e-3) / 1e9 if enc_ms else 0.0}
+                "hbm_GBps": enc_bytes / (enc_ms * 1e-3) / 1e9 if enc_ms else 0.0,
+                "hbm_frac": enc_bytes / (enc_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if enc_ms else 0.0}
     roofline_agg = {"kernel": "k_aggregate", "bound": "hbm", "achieved": agg_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": agg_gbs / HBM_PEAK_GBS, "traffic": traffic.get("k_aggregate"),
-                    "valu_busy_pct_profiled": measured_valu_busy(w.name).get("k_aggregate"),
+                    "valu_busy_pct_profiled": busy.get("k_aggregate"), "profiled_fields": prof_note,
                     "algorithmic_bytes_per_launch": agg_bytes / max(agg_launches, 1),
-                    "avg_launch_ms": agg_ms / max(agg_launches, 1), "launches": int(agg_launches)}
+                    "avg_launch_ms": agg_ms / max(agg_launches, 1), "launches": int(agg_launches),
+                    "target_hbm_frac": 0.6, "met": bool(agg_gbs / HBM_PEAK_GBS >= 0.6)}
+    # the plaintext path (HBM-bound): compaction / scatter of the remainder and its float64 averaging
+    mv_ms, mv_launches = kern.get("plain_move", (0.0, 0))
+    pf_ms, pf_launches = kern.get("plain_fedavg", (0.0, 0))
+    mv_bytes = 8 * n_pl * (K + 1) * steps                               # K compactions and one scatter: 4 B read + 4 B written each
+    if streamed:   # folds of G clients: K reads, an accumulator read + write per fold, the final read + float32 write
+        folds = -(-K // G)
+        pf_bytes = n_pl * (4 * K + 16 * folds + 8 + 4) * steps
+    else:
+        pf_bytes = n_pl * (4 * K + 4) * steps
+    roofline_plain = None
+    if n_pl:
+        roofline_plain = {
+            "k_plain_move": {"bound": "hbm", "achieved": mv_bytes / (mv_ms * 1e-3) / 1e9 if mv_ms else 0.0, "peak": HBM_PEAK_GBS,
+                             "unit": "GB/s", "frac": mv_bytes / (mv_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if mv_ms else 0.0,
+                             "frac_of_copy_ceiling": mv_bytes / (mv_ms * 1e-3) / 1e9 / COPY_CEILING_GBS if mv_ms else 0.0,
+                             "avg_launch_ms": mv_ms / max(mv_launches, 1), "launches": int(mv_launches),
+                             "note": "K compactions (he_encrypt_masked) and one scatter (he_decrypt_merge), 4 B read + 4 B written per plaintext parameter each"},
+            "k_plain_fedavg": {"bound": "hbm", "achieved": pf_bytes / (pf_ms * 1e-3) / 1e9 if pf_ms else 0.0, "peak": HBM_PEAK_GBS,
+                               "unit": "GB/s", "frac": pf_bytes / (pf_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if pf_ms else 0.0,
+                               "avg_launch_ms": pf_ms / max(pf_launches, 1), "launches": int(pf_launches)}}
+    # encoder and decoder: fp64 FFT through LDS plus (decoder) the exact lift; reported against their fp64 / integer
+    # operation counts
+    ec_ms, ec_launches = kern.get("encode", (0.0, 0))
+    dc_ms, dc_launches = kern.get("decode", (0.0, 0))
+    dq_ms, dq_launches = kern.get("decrypt", (0.0, 0))
+    side = {"encode_ms_per_step": ec_ms / steps, "decode_ms_per_step": dc_ms / steps, "decrypt_ms_per_step": dq_ms / steps,
+            "encode_cts_per_s": n_ct * K * steps / (ec_ms * 1e-3) if ec_ms else 0.0,
+            "decode_cts_per_s": n_ct * steps / (dc_ms * 1e-3) if dc_ms else 0.0,
+            "decrypt_cts_per_s": n_ct * steps / (dq_ms * 1e-3) if dq_ms else 0.0}
 
-    n_pl = mask.n_plain
     phase_bytes = [K * (4 * P_enc + 8 * n_pl + n_ct * 8 * L * N),                       # parameters read, remainder copied, ciphertexts written
                    n_ct * 8 * N * (K * L + L_out) + n_pl * (4 * K + 4),               # K ciphertexts and remainders read, one of each written
                    n_ct * 8 * L_out * N + 4 * P_enc + 8 * n_pl]                        # ciphertext read, parameters written, remainder copied
@@ -487,13 +485,14 @@ def main():
         phase_bytes[0] += n_pl * 4 * K
         phase_bytes[1] -= n_pl * 4 * K
     res = {
-        "metric": "encrypted params/sec (encrypt, aggregate, decrypt) + NTT/agg HBM GB/s % of peak",
-        "value": K * P_enc / (ms_step * 1e-3), "unit": "params/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "u32", "data": "synthetic",
-        "config": {"workload": w.name, "variant": args.variant, "streamed_clients": streamed, "client_streams": S, "distinct_client_vectors": n_distinct, "clients": K, "params_per_client": w.n_params, "encrypted_params": P_enc,
+        "value": K * P_enc / (ms_step * 1e-3), "unit": "params/s", "ms_per_step": ms_step, "steps": steps, "warmup": warmup,
+        "whole_model_params_per_s": K * w.n_params / (ms_step * 1e-3),
+        "config": {"workload": w.name, "variant": args.variant, "streamed_clients": streamed, "client_streams": S,
+                   "distinct_client_vectors": n_distinct, "clients": K, "params_per_client": w.n_params, "encrypted_params": P_enc,
                    "n_ct_per_client": n_ct, "ring_degree": N, "limbs": L, "scale_bits": w.scale_bits,
-                   "value_definition": "clients * encrypted_params / step time; step = all clients encrypt + aggregate + decrypt"},
+                   "value_definition": "clients * encrypted_params / step time; step = all clients encrypt + aggregate + decrypt; "
+                                       "whole_model_params_per_s = clients * params_per_client / the same step time (gather, "
+                                       "plaintext FedAvg and merge of the unencrypted share included)"},
         "phases": {"encrypt_ms": phase_ms[0], "aggregate_ms": phase_ms[1], "decrypt_ms": phase_ms[2],
                    "encrypt_params_per_s": K * P_enc / (phase_ms[0] * 1e-3),
                    "aggregate_params_per_s": P_enc / (phase_ms[1] * 1e-3),
@@ -504,19 +503,146 @@ def main():
                    "decrypt_frac_of_hbm_roofline": phase_bytes[2] / (phase_ms[2] * 1e-3) / (HBM_PEAK_GBS * 1e9)},
         "uninstrumented": {"ms_per_step": ms_step_plain, "value": K * P_enc / (ms_step_plain * 1e-3),
                            "note": "same steps without the per-kernel event pairs and phase events of the timed region"},
-        "kernels_ms_per_step": {k: v[0] / args.steps for k, v in kern.items() if v[1]},
+        "kernels_ms_per_step": {k: v[0] / steps for k, v in kern.items() if v[1]},
         "dominant_kernel": dominant,
-        "roofline": roofline, "roofline_aggregate": roofline_agg, "roofline_ntt": roofline_ntt,
+        "roofline": roofline, "roofline_aggregate": roofline_agg, "roofline_plain": roofline_plain, "encode_decode": side,
         "max_abs_err_vs_float64_fedavg": max_err,
     }
-    if k_sweep is not None:
-        res["aggregate_k_sweep"] = k_sweep
-    if param_sweep is not None:
-        res["crypto_param_sweep"] = param_sweep
-    if select_rows is not None:
-        res["mask_select"] = select_rows
-    if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(w, ws_host, alpha, runs, client_weighted=client_weighted)
+    if headline:
+        res["roofline_ntt"] = ntt_rooflines(he, ctx, torch, w.name)
+        if args.calibrate_copy:
+            src = torch.empty(1 << 28, dtype=torch.int32, device="cuda").fill_(1)   # 1 GiB
+            dst = torch.empty_like(src)
+            dst.copy_(src)
+            torch.cuda.synchronize()
+            del src, dst
+        if args.k_sweep:
+            res["aggregate_k_sweep"] = aggregate_k_sweep(he, ctx, torch)
+        if args.param_sweep:
+            res["crypto_param_sweep"] = crypto_param_sweep(he, torch)
+        if args.select_bench:
+            res["mask_select"] = mask_select_bench(he, ctx, torch)
+        if not args.no_cpu_baseline:
+            from oracle import fedavg as ofed                                  # host index arithmetic of the gather only
+            n = N // 2
+            uniq = {id(x): x for x in ws}
+
+            def slots_of(c):
+                t = np.arange(c * n, min((c + 1) * n, P_enc))
+                idx = torch.from_numpy(ofed.packed_to_param(starts, lens, t)).cuda()
+                got = {k: np.concatenate([x[idx].double().cpu().numpy(), np.zeros(n - len(t))]) for k, x in uniq.items()}
+                return [got[id(x)] for x in ws]
+
+            res["cpu_baseline"] = cpu_baseline(w, slots_of, n_ct, alpha, client_weighted=client_weighted)
+    del cts, plains, ct_g, pl_g, out, ws, acc_plain, acc_none
+    for c2, k2, m2, _ in lanes[1:]:
+        k2.close(), m2.close(), c2.close()
+    keys.close(), mask.close(), ctx.close()
+    if server is not None:
+        server.close()
+    torch.cuda.empty_cache()
+    return res
+
+
+def ntt_rooflines(he, ctx, torch, workload, batch=4096, reps=5):
+    """Standalone transform (he_debug_ntt, in place): forward and inverse timed separately over `batch` polynomials.
+    8 B of HBM traffic per coefficient (one read, one write); reported against the HBM peak, which is what the 60 %
+    target refers to, and against the integer ALU peak, which is what bounds the kernel."""
+    N, L = ctx.N, ctx.L
+    log_n = N.bit_length() - 1
+    polys = torch.randint(0, ctx.primes[-1], (batch, N), dtype=torch.int32, device="cuda")
+    out = {}
+    for inverse, tag in ((False, "forward"), (True, "inverse")):
+        he.he_debug_ntt(ctx, inverse, L - 1, polys)
+        torch.cuda.synchronize()
+        he.he_debug_timing_enable(ctx, True)
+        he.he_debug_timing_read(ctx)
+        for _ in range(reps):
+            he.he_debug_ntt(ctx, inverse, L - 1, polys)
+        ms, launches = he.he_debug_timing_read(ctx)["ntt"]
+        he.he_debug_timing_enable(ctx, False)
+        coeff_per_s = batch * N * launches / (ms * 1e-3)
+        ops = (0.5 * log_n * OPS_BFLY_INV + OPS_LAST_STAGE_NINV) if inverse else fwd_ops_per_coeff(log_n, False)
+        tops = coeff_per_s * ops / 1e12
+        hbm_frac = coeff_per_s * 8 / 1e9 / HBM_PEAK_GBS
+        out[tag] = {"kernel": "k_ntt_batch_s<%d,%s>" % (log_n, "true" if inverse else "false"), "bound": "alu",
+                    "achieved": tops, "peak": ALU_PEAK_TOPS, "unit": "TOP/s", "frac": tops / ALU_PEAK_TOPS,
+                    "ops_per_coeff": ops, "coeff_per_s": coeff_per_s, "avg_launch_ms": ms / launches, "launches": int(launches),
+                    "algorithmic_bytes_per_launch": batch * N * 8, "hbm_GBps": coeff_per_s * 8 / 1e9, "hbm_frac": hbm_frac,
+                    "hbm_frac_ceiling_at_perfect_issue": ALU_PEAK_TOPS * 1e12 / ops * 8 / 1e9 / HBM_PEAK_GBS,
+                    "target_hbm_frac": 0.6, "met": bool(hbm_frac >= 0.6),
+                    "traffic": measured_traffic(workload).get("k_ntt_batch_" + tag),
+                    "valu_busy_pct_profiled": measured_valu_busy(workload).get("k_ntt_batch_" + tag)}
+    del polys
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default=None,
+                    help=f"headline workload (default: {HEADLINE}, the largest one, or bert_full when less than "
+                         f"{HEADLINE_MIN_FREE_GIB} GiB of HBM are free)")
+    ap.add_argument("--only", action="store_true", help="run the headline workload only (no rows for the other workloads)")
+    ap.add_argument("--other-steps", type=int, default=5, help="timed steps of each of the other workloads' rows")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--variant", default="server_weighted", choices=["server_weighted", "client_weighted"],
+                    help="client_weighted: clients encode alpha_i * W_i, the server only adds ciphertexts (no rescale), one limb fewer")
+    ap.add_argument("--param-sweep", action="store_true",
+                    help="also run packing batch 1024..8192 x scaling bits 20/30 on a 1.66M-parameter vector, 3 clients")
+    ap.add_argument("--select-bench", action="store_true",
+                    help="also time the encryption-mask selection (top-p of a sensitivity map) on 25.6M / 110M / 1.3B entries")
+    ap.add_argument("--k-sweep", action="store_true",
+                    help="also time he_aggregate alone for K = 3 ... 200 clients (server cost against the number of clients)")
+    ap.add_argument("--stream-clients", action="store_true",
+                    help="fold each client's plaintext remainder into the server's accumulator right after its encryption "
+                         "(he_aggregate_begin/add/finalize) and keep only 4 distinct client vectors resident; chosen by "
+                         "itself when the clients' vectors exceed 64 GB")
+    ap.add_argument("--fold-group", type=int, default=16, help="streamed clients: remainders the server folds per he_aggregate_add")
+    ap.add_argument("--fold-buffers", type=int, default=1, help="streamed clients: groups of remainder buffers (2 = the next group encrypts while one is folded)")
+    ap.add_argument("--client-streams", type=int, default=1,
+                    help="number of clients that encrypt side by side, each on its own context and stream (default 1: one after the other)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (known HBM traffic, for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (ciphertext indices are independent, so more GPUs "
+                 "would shard by ciphertext index with no collectives); run with --gpus 1")
+
+    import torch
+    from paper_2303_10837_amd import binding as he, synth_inputs as si
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    free_gib = torch.cuda.mem_get_info()[0] / 2 ** 30
+    name, fallback = args.workload, None
+    if name is None:
+        name = HEADLINE
+        if free_gib < HEADLINE_MIN_FREE_GIB:
+            name, fallback = "bert_full", f"{HEADLINE} needs {HEADLINE_MIN_FREE_GIB} GiB of free HBM, this GPU has {free_gib:.0f}"
+    head = run_workload(he, si, torch, name, args, args.steps, args.warmup, True)
+    res = {"metric": "encrypted params/sec (encrypt, aggregate, decrypt) + NTT/agg HBM GB/s % of peak",
+           "value": head.pop("value"), "unit": head.pop("unit"), "n_gpus": 1, "steps": head.pop("steps"),
+           "warmup": head.pop("warmup"), "ms_per_step": head.pop("ms_per_step"), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "u32", "data": "synthetic"}
+    res.update(head)
+    res["config"]["free_hbm_gib_at_start"] = free_gib
+    if fallback:
+        res["config"]["headline_fallback"] = fallback
+    if not args.only and args.workload is None:
+        rows = {}
+        keep = ("value", "unit", "ms_per_step", "steps", "whole_model_params_per_s", "phases", "uninstrumented", "kernels_ms_per_step",
+                "dominant_kernel", "roofline", "roofline_aggregate", "roofline_plain", "encode_decode", "max_abs_err_vs_float64_fedavg")
+        for other in OTHER_WORKLOADS:
+            if other == name:
+                continue
+            r = run_workload(he, si, torch, other, args, args.other_steps, 1, False)
+            rows[other] = {k: r[k] for k in keep}
+            rows[other]["config"] = {k: r["config"][k] for k in ("clients", "params_per_client", "encrypted_params", "n_ct_per_client",
+                                                                  "ring_degree", "limbs", "streamed_clients")}
+        res["workloads"] = rows
     print(json.dumps(res))
 
 

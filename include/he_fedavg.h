@@ -23,14 +23,14 @@
  *  - All GPU work is enqueued on the given stream (a hipStream_t passed as void*; NULL is
  *    the default stream).  Calls are asynchronous with respect to the host except where a
  *    function says otherwise.  A context owns scratch memory: calls that share a context
- *    must be issued on one stream (or be externally ordered).  he_encrypt_masked and
- *    he_decrypt_merge run the copy of the plaintext remainder on a stream of the context's
- *    own (default priority), forked from and joined back into the given stream before the
- *    call returns, so the ordering the caller sees is that of the given stream.
- *    The calls of the round (he_encrypt_masked, he_aggregate*, he_decrypt_merge*) can be recorded
- *    into a HIP graph by stream capture once a first eager call with the same sizes has grown the
- *    context's scratch: after that they allocate nothing, synchronise nothing and clear memory with
- *    kernels.  The set-up calls (contexts, keys, masks) cannot.
+ *    must be issued on one stream (or be externally ordered).  The scratch grows on demand:
+ *    the FIRST call on a context that needs more of it than any call before (a larger model,
+ *    more than 64 clients) waits for the whole device (hipDeviceSynchronize), frees the old
+ *    block and allocates a larger one; every later call of that size or smaller is fully
+ *    asynchronous.  The calls of the round (he_encrypt_masked, he_aggregate*, he_decrypt_merge*)
+ *    can be recorded into a HIP graph by stream capture once such a first eager call with the
+ *    same sizes has been made: after that they allocate nothing, synchronise nothing and clear
+ *    memory with kernels.  The set-up calls (contexts, keys, masks) cannot.
  *  - Ring: R = Z[X]/(X^N+1), N = 2^log2_n, n = N/2 slots per ciphertext (the paper's
  *    "packing batch size").  Modulus chain q_0 > ... > q_{L-1}, primes < 2^31, q = 1 mod 2N.
  *  - Ciphertext layout: uint32 [n_ct][2][level][N], coefficient domain, residues in [0,q_j),
@@ -43,6 +43,18 @@
  *    kept compacted in parameter order: float32 [P - P_enc].
  *  - Randomness: Philox4x32-10, key = seed, counter = (block, ciphertext index, client id,
  *    stream tag); outputs are a pure function of (params, seed, client id, inputs).
+ *    SECURITY: the encryption randomness (u, e0, e1) of a ciphertext is a function of
+ *    (seed, client id, ciphertext index) ONLY.  Algorithm 1 keeps one key pair for all T rounds,
+ *    so every he_encrypt_masked* call under one key must get a (seed, client id) pair that was
+ *    never used before -- a fresh seed per round -- and that is unrelated to the he_keygen seed.
+ *    Two calls with the same pair yield ciphertexts with identical c1 and c0 - c0' = m - m':
+ *    whoever sees both reads the difference of the two updates without any key.  The library
+ *    keeps no state between calls and cannot detect the reuse.
+ *  - Ciphertext inputs of the server calls (he_aggregate*, and he_decrypt_merge*) must hold
+ *    canonical residues, every word of limb j in [0, q_j): the aggregation accumulates four
+ *    products w * x in 64 bits before it reduces, which is exact only for x < 2^31.  Buffers from
+ *    he_encrypt_masked* and he_aggregate* satisfy this by construction; a buffer from elsewhere
+ *    (the network) can be checked with he_debug_count_noncanonical.
  *  - Input parameters must be finite with |x| * 2^scale_bits < 2^31 (not checked on the
  *    hot path).
  */
@@ -99,7 +111,8 @@ uint64_t he_ct_bytes(const he_ctx* ctx, uint32_t level);        /* 2 * level * N
 /* ---- HE.KeyGen (Algorithm 1, "Key Authority Generate Key") ---------------------------- */
 
 /* s ternary, a_j uniform, e centred binomial; b_j = -(a_j * s) + e mod q_j.  Keys live on
-   the device in the transform domain.  Asynchronous on `stream`. */
+   the device in the transform domain.  Set-up call: allocates the key tables and a temporary,
+   enqueues on `stream` and waits for it (hipStreamSynchronize) before it returns. */
 he_status he_keygen(he_ctx* ctx, uint64_t seed, he_pk** pk, he_sk** sk, void* stream);
 void he_pk_destroy(he_pk* pk);
 void he_sk_destroy(he_sk* sk);
@@ -258,6 +271,12 @@ he_status he_debug_export_keys(he_ctx* ctx, const he_pk* pk, const he_sk* sk,
    context's scratch like every other call. */
 he_status he_debug_count_out_of_range(he_ctx* ctx, const float* w_dev, uint64_t n,
                                       uint64_t* count_host, void* stream);
+
+/* Precondition check for the server calls: counts the words of ct_dev uint32[n_ct][2][level][N]
+   that are not canonical residues (word >= q_j in limb j).  Synchronous on `stream`; uses the
+   context's scratch. */
+he_status he_debug_count_noncanonical(he_ctx* ctx, const uint32_t* ct_dev, uint64_t n_ct,
+                                      uint32_t level, uint64_t* count_host, void* stream);
 
 /* Per-kernel device timing for benchmarks: while enabled, every kernel launch of this
    context is bracketed by a pair of HIP events on its stream.  he_debug_timing_read waits

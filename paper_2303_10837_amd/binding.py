@@ -66,6 +66,7 @@ _SIGS = {
     "he_debug_ntt": (C.c_int32, [_P, C.c_int, C.c_uint32, _P, C.c_uint64, _P]),
     "he_debug_export_keys": (C.c_int32, [_P, _P, _P, _P, _P, _P]),
     "he_debug_count_out_of_range": (C.c_int32, [_P, _P, C.c_uint64, C.POINTER(C.c_uint64), _P]),
+    "he_debug_count_noncanonical": (C.c_int32, [_P, _P, C.c_uint64, C.c_uint32, C.POINTER(C.c_uint64), _P]),
     "he_debug_timing_enable": (C.c_int32, [_P, C.c_int]),
     "he_debug_timing_kernels": (C.c_uint32, []),
     "he_debug_timing_name": (C.c_char_p, [C.c_uint32]),
@@ -211,7 +212,11 @@ def he_mask_runs(mask):
 
 
 def he_encrypt_masked(ctx, keys, mask, seed, client_id, w, ct_out=None, plain_out=None):
-    """Returns (ct int32-viewed-uint32 [n_ct,2,L,N], plain float32[P-P_enc])."""
+    """Returns (ct int32-viewed-uint32 [n_ct,2,L,N], plain float32[P-P_enc]).
+
+    (seed, client_id) must be fresh for every call under one key pair (a new seed every round) and unrelated to the
+    he_keygen seed: the encryption randomness depends on nothing else, and reusing a pair leaks the difference of the
+    two plaintexts (see include/he_fedavg.h)."""
     if ct_out is None:
         ct_out = torch.empty((mask.n_ct, 2, ctx.L, ctx.N), dtype=torch.int32, device=ctx.device)
     if plain_out is None:
@@ -381,6 +386,12 @@ def he_debug_export_keys(ctx, keys):
 def he_debug_count_out_of_range(ctx, w):
     n = C.c_uint64(0)
     _check(load().he_debug_count_out_of_range(ctx.h, _ptr(w, torch.float32) if w.numel() else None, w.numel(), C.byref(n), _stream()))
+    return int(n.value)
+
+
+def he_debug_count_noncanonical(ctx, ct, level):
+    n = C.c_uint64(0)
+    _check(load().he_debug_count_noncanonical(ctx.h, _ptr(ct, torch.int32) if ct.numel() else None, ct.shape[0], level, C.byref(n), _stream()))
     return int(n.value)
 
 

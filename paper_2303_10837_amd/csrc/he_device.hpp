@@ -41,21 +41,19 @@ __device__ __forceinline__ uint32_t mul_shoup(uint32_t y, uint2 w, uint32_t q) {
 
 // The same product in three instructions instead of four: w*y as a full 64-bit multiply-add
 // (v_mad_u64_u32, full rate on gfx950), then a second one adds hi * (2^32 - q); the low word is
-// w*y - hi*q mod 2^32.  Written as inline assembly because the compiler narrows the pattern back
-// to a 32-bit multiply and a subtraction.  W_SCALAR: w is wave-uniform and sits in scalar
-// registers (a VOP3 instruction takes one scalar source).  Measured 44.1 against 47.3 cycles per
-// wave64 butterfly.
+// w*y - hi*q mod 2^32.  Left to itself the compiler sees that only the low word is used and narrows
+// the pattern back to a 32-bit multiply and a subtraction; the empty asm statement below makes all
+// 64 bits of the sum count as used and emits nothing.  Written as ordinary arithmetic (not as
+// inline-assembly instructions) so that the scheduler knows the multiply-adds' latency and fills
+// the wait state a dependent instruction needs after them with independent work instead of s_nop.
+// W_SCALAR documents that w is wave-uniform (the compiler keeps it in scalar registers by itself).
+// Measured 44.1 against 47.3 cycles per wave64 butterfly.
 template <bool W_SCALAR>
 __device__ __forceinline__ uint32_t mul_shoup_lazy_mad(uint32_t y, uint2 w, uint32_t q) {
   const uint32_t hi = __umulhi(w.y, y);
-  const uint32_t negq = 0u - q;
-  uint64_t acc, carry;
-  if constexpr (W_SCALAR) {
-    asm("v_mad_u64_u32 %0, %1, %2, %3, 0" : "=v"(acc), "=s"(carry) : "s"(w.x), "v"(y));
-  } else {
-    asm("v_mad_u64_u32 %0, %1, %2, %3, 0" : "=v"(acc), "=s"(carry) : "v"(w.x), "v"(y));
-  }
-  asm("v_mad_u64_u32 %0, %1, %2, %3, %0" : "+v"(acc), "=s"(carry) : "v"(hi), "s"(negq));
+  uint64_t acc = (uint64_t)w.x * y;
+  acc += (uint64_t)hi * (uint32_t)(0u - q);
+  asm("" : "+v"(acc));
   return (uint32_t)acc;
 }
 

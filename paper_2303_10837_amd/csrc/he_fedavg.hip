@@ -29,6 +29,7 @@ struct RingDev {
   uint32_t logN, N, L, scale_bits, eta;
   uint32_t q[kMaxLimbs];
   uint2 ninv[kMaxLimbs];     // N^-1 mod q_j (+ Shoup companion)
+  uint2 ninv_w1[kMaxLimbs];  // psi_j^-bitrev(1) * N^-1 mod q_j: last-stage twiddle of a standalone inverse transform
   const uint2* tw_fwd;       // [L][N]  psi^bitrev(k)
   const uint2* tw_inv;       // [L][N]  psi^-bitrev(k)
   const double2* fft_e;      // [n/2]   exp(-2 pi i r / n)
@@ -356,30 +357,43 @@ __device__ __forceinline__ void load_key8(const uint2* __restrict__ key, int bas
   }
 }
 
+// w_i = v_i * key[base + i] mod q for 8 consecutive table entries, four at a time (16-byte loads; eight entries
+// at once would hold 16 registers the kernel does not have).
+__device__ __forceinline__ void key_product8(const uint2* __restrict__ key, int base, const uint32_t (&v)[8], uint32_t (&w)[8],
+                                             uint32_t q) {
+  const uint4* p = reinterpret_cast<const uint4*>(key + base);
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const uint4 t0 = p[2 * h], t1 = p[2 * h + 1];
+    w[4 * h + 0] = mul_shoup_mad<false>(v[4 * h + 0], make_uint2(t0.x, t0.y), q);
+    w[4 * h + 1] = mul_shoup_mad<false>(v[4 * h + 1], make_uint2(t0.z, t0.w), q);
+    w[4 * h + 2] = mul_shoup_mad<false>(v[4 * h + 2], make_uint2(t1.x, t1.y), q);
+    w[4 * h + 3] = mul_shoup_mad<false>(v[4 * h + 3], make_uint2(t1.z, t1.w), q);
+  }
+}
+
 // One LDS buffer per workgroup (two workgroups per CU) and at most 64 registers per thread (8
 // waves per SIMD): the kernel waits on table loads from L2 most of the time it is not computing,
 // and resident waves are what hides that.  The two inverse transforms (c0, c1) run one after the
-// other through the same buffer; after the fused middle pass the second polynomial waits in this
-// workgroup's own c1 output row (written and read back by the same thread, normally from L2).
+// other through the same buffer; after the fused middle pass the second polynomial waits in
+// registers (16 per thread), so the kernel's only global traffic is its inputs, tables and outputs.
 template <int LOGN>
 __global__ void __launch_bounds__(NttPlan<LOGN>::NT, 8)
 k_encrypt_s(RingDev rg, const uint2* __restrict__ pk, const int8_t* __restrict__ u, const int32_t* __restrict__ m,
-            const int8_t* __restrict__ e0, const int8_t* __restrict__ e1, uint32_t* __restrict__ ct_out, uint32_t n_ct,
-            uint32_t cts_per_slot) {
+            const int8_t* __restrict__ e0, const int8_t* __restrict__ e1, uint32_t* __restrict__ ct_out, uint32_t n_ct) {
   using P = NttPlan<LOGN>;
   constexpr int N = 1 << LOGN, NT = P::NT;
   extern __shared__ uint32_t lds_u[];
   uint32_t* A = lds_u;
   const uint32_t L = rg.L;
   // Workgroups are dealt to the 8 XCDs round-robin by linear id (id = slot * 8 + xcd), and each XCD has its own L2.
-  // When L divides 8 (cts_per_slot = 8 / L) every XCD works on ONE limb, xcd % L: its L2 then holds the twiddle and
-  // key tables of that limb only (512 KiB instead of 2 MiB at N = 2^14, L = 4) beside the parked polynomials, and
-  // the tables stop being evicted and fetched again; that u / m / e0 / e1 of a ciphertext are now read on L XCDs
-  // costs less (they are small and recent).  Measured: encrypt 5.74 -> 5.56 ms per 8 x 1429 ciphertexts.
-  // Otherwise the L limb-workgroups of a ciphertext sit on one XCD at consecutive slots.
+  // The L limb-workgroups of a ciphertext sit on ONE XCD at consecutive slots, so that the ciphertext's inputs
+  // (u, m, e0, e1: 7 N bytes) leave HBM once and the other L - 1 workgroups find them in that XCD's L2: measured
+  // 1.10 x the algorithmic bytes, against 1.5 x when every XCD works on one limb (which keeps less table data per L2,
+  // 512 KiB instead of 2 MiB at N = 2^14, L = 4, but reads the inputs on L XCDs) and 2 % faster.
   const uint32_t slot = blockIdx.x >> 3, xcd = blockIdx.x & 7;
-  const uint32_t j = cts_per_slot ? xcd % L : slot % L;
-  const uint64_t c = cts_per_slot ? (uint64_t)slot * cts_per_slot + xcd / L : (uint64_t)(slot / L) * 8 + xcd;
+  const uint32_t j = slot % L;
+  const uint64_t c = (uint64_t)(slot / L) * 8 + xcd;
   if (c >= n_ct) return;  // whole workgroup leaves before any barrier
   const uint32_t q = rg.q[j];
   const uint2* twf = rg.tw_fwd + (size_t)j * N;
@@ -391,7 +405,10 @@ k_encrypt_s(RingDev rg, const uint2* __restrict__ pk, const int8_t* __restrict__
   constexpr int S3 = P::S[3], R3 = P::R[3];
   static_assert(R3 == 3, "the fused middle pass works on groups of 8");
   constexpr int IT3 = OwnedIters<LOGN, 3, NT>::value;
-  {  // forward pass 3, product with b^ / a^, inverse pass 3: all on the same 8 coefficients
+  // Forward pass 3, product with b^ / a^, inverse pass 3: all on the same 8 coefficients.  The first polynomial goes
+  // back to LDS; the second one (16 words per thread) waits in registers until the first has left the buffer.
+  uint32_t parked[IT3][8];
+  {
     const uint2* kb = pk + ((size_t)0 * L + j) * N;
     const uint2* ka = pk + ((size_t)1 * L + j) * N;
 #pragma unroll
@@ -400,20 +417,14 @@ k_encrypt_s(RingDev rg, const uint2* __restrict__ pk, const int8_t* __restrict__
       uint32_t v[1][8];
       lds_load_group<LOGN, S3, R3>(A, g, v[0]);
       bfly_stages<LOGN, S3, R3, false, 1, true>(v, g, twf, q);
-      uint2 k[8];
       uint32_t w[1][8];
-      load_key8(kb, g << 3, k);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) w[0][i] = mul_shoup_mad<false>(v[0][i], k[i], q);
+      key_product8(kb, g << 3, v[0], w[0], q);
       bfly_stages<LOGN, S3, R3, true, 1>(w, g, twi, q);
       lds_store_group<LOGN, S3, R3>(A, g, w[0]);
-      load_key8(ka, g << 3, k);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) w[0][i] = mul_shoup_mad<false>(v[0][i], k[i], q);
+      key_product8(ka, g << 3, v[0], w[0], q);
       bfly_stages<LOGN, S3, R3, true, 1>(w, g, twi, q);
-      uint4* park = reinterpret_cast<uint4*>(out1 + (g << 3));
-      park[0] = make_uint4(w[0][0], w[0][1], w[0][2], w[0][3]);  // ordinary stores: non-temporal ones measured 2 % slower
-      park[1] = make_uint4(w[0][4], w[0][5], w[0][6], w[0][7]);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) parked[it][i] = w[0][i];
     }
   }
   uint32_t* const xs[1] = {A};
@@ -427,13 +438,7 @@ k_encrypt_s(RingDev rg, const uint2* __restrict__ pk, const int8_t* __restrict__
     if (poly == 1) {
       __syncthreads();  // every wave's reads of the first polynomial are done
 #pragma unroll
-      for (int it = 0; it < IT3; ++it) {
-        const int g = owned_group<LOGN, 3, NT>(it);
-        const uint4* park = reinterpret_cast<const uint4*>(out1 + (g << 3));
-        const uint4 p0 = park[0], p1 = park[1];
-        const uint32_t back[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
-        lds_store_group<LOGN, S3, R3>(A, g, back);
-      }
+      for (int it = 0; it < IT3; ++it) lds_store_group<LOGN, S3, R3>(A, owned_group<LOGN, 3, NT>(it), parked[it]);
     }
     inv_middle<LOGN, 1, NT>(xs, twi, q);
     uint32_t* out = poly == 0 ? out0 : out1;
@@ -509,7 +514,7 @@ k_decrypt_s(RingDev rg, const uint2* __restrict__ sk, const uint32_t* __restrict
 }
 
 template <int LOGN, bool INV>
-__global__ void __launch_bounds__(NttPlan<LOGN>::NT)
+__global__ void __launch_bounds__(NttPlan<LOGN>::NT, 8)
 k_ntt_batch_s(RingDev rg, int limb, uint32_t* __restrict__ polys) {
   using P = NttPlan<LOGN>;
   constexpr int N = 1 << LOGN;
@@ -534,7 +539,7 @@ k_ntt_batch_s(RingDev rg, int limb, uint32_t* __restrict__ polys) {
     }
   } else {
     const uint2* twi = rg.tw_inv + (size_t)j * N;
-    const uint2 ninv = rg.ninv[j];
+    const uint2 ninv = rg.ninv[j], ninv_w1 = rg.ninv_w1[j];
 #pragma unroll
     for (int it = 0; it < OwnedIters<LOGN, 3, P::NT>::value; ++it) {
       const int g = owned_group<LOGN, 3, P::NT>(it);
@@ -555,9 +560,9 @@ k_ntt_batch_s(RingDev rg, int limb, uint32_t* __restrict__ polys) {
     for (int g = threadIdx.x; g < G0::GROUPS; g += P::NT) {
       uint32_t v[1][1 << R0];
       lds_load_group<LOGN, 0, R0>(A, g, v[0]);
-      bfly_stages<LOGN, 0, R0, true, 1>(v, 0, twi, q);
+      bfly_stages<LOGN, 0, R0, true, 1, false, true>(v, 0, twi, q, ninv, ninv_w1);
 #pragma unroll
-      for (int i = 0; i < G0::E; ++i) x[g + (i << G0::LSTRIDE)] = mul_shoup(v[0][i], ninv, q);
+      for (int i = 0; i < G0::E; ++i) x[g + (i << G0::LSTRIDE)] = v[0][i];
     }
   }
 }
@@ -1076,6 +1081,20 @@ k_count_out_of_range(const float* __restrict__ w, uint64_t n, double delta, unsi
   if ((threadIdx.x & 63) == 0 && bad) atomicAdd(count, (unsigned long long)bad);
 }
 
+// Counts the words of ciphertext rows [rows][N] (row r belongs to limb r % level) that are not below their prime.
+__global__ void __launch_bounds__(256)
+k_count_noncanonical(RingDev rg, const uint32_t* __restrict__ ct, uint64_t n_words, uint32_t level,
+                     unsigned long long* __restrict__ count) {
+  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+  uint32_t bad = 0;
+  for (uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; t < n_words; t += stride) {
+    const uint32_t j = (uint32_t)((t >> rg.logN) % level);
+    if (ct[t] >= rg.q[j]) ++bad;
+  }
+  for (int d = 32; d > 0; d >>= 1) bad += __shfl_down(bad, d, 64);
+  if ((threadIdx.x & 63) == 0 && bad) atomicAdd(count, (unsigned long long)bad);
+}
+
 // =========================================================================================
 // Host side
 // =========================================================================================
@@ -1144,10 +1163,6 @@ struct he_ctx {
   size_t ws_bytes = 0;
   void* static_scratch = nullptr;  // this GPU's copy of the file-scope array `scratch`
   int max_lds = 0;
-  // The plaintext remainder (an HBM-bound copy) runs beside the ALU-bound transform kernels on a
-  // second stream of the context's own, forked from and joined back into the caller's stream.
-  hipStream_t side = nullptr;
-  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
 };
 
 struct he_pk {
@@ -1255,19 +1270,6 @@ he_status check_ctx(const he_ctx* ctx) {
   return HE_OK;
 }
 
-// Work launched on ctx->side between fork and join runs concurrently with what the caller's
-// stream does in between, and is ordered before everything the caller enqueues after join.
-he_status side_fork(he_ctx* ctx, hipStream_t st) {
-  HIP_TRY(hipEventRecord(ctx->ev_fork, st));
-  HIP_TRY(hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0));
-  return HE_OK;
-}
-he_status side_join(he_ctx* ctx, hipStream_t st) {
-  HIP_TRY(hipEventRecord(ctx->ev_join, ctx->side));
-  HIP_TRY(hipStreamWaitEvent(st, ctx->ev_join, 0));
-  return HE_OK;
-}
-
 // ---- shared launch helpers ---------------------------------------------------------------
 
 void launch_ntt_batch(const RingDev& rg, bool inverse, int limb, uint32_t* polys, uint32_t batch, hipStream_t st) {
@@ -1350,15 +1352,14 @@ he_status launch_encrypt(he_ctx* ctx, const he_pk* pk, uint64_t n_ct, const int3
   const RingDev& rg = ctx->ring;
   KernelTimer timer_(ctx, KID_ENCRYPT, st);
   const dim3 grid(rg.L, (uint32_t)n_ct);
-  // XCD-aware linear grid, see k_encrypt_s: one limb per XCD when L divides 8
-  const uint32_t cts_per_slot = (8 % rg.L == 0) ? 8 / rg.L : 0;
-  const dim3 grid_x(cts_per_slot ? (uint32_t)((n_ct + cts_per_slot - 1) / cts_per_slot) * 8 : (uint32_t)((n_ct + 7) / 8) * 8 * rg.L);
+  // XCD-aware linear grid, see k_encrypt_s: 8 ciphertexts (one per XCD) x L limbs per group of 8 L workgroups
+  const dim3 grid_x((uint32_t)((n_ct + 7) / 8) * 8 * rg.L);
   if (rg.logN == 14)
     hipLaunchKernelGGL(k_encrypt_s<14>, grid_x, dim3(NttPlan<14>::NT), static_lds_bytes(14, 1), st, rg, pk->tab, rnd.u, m, rnd.e0, rnd.e1,
-                       ct_out, (uint32_t)n_ct, cts_per_slot);
+                       ct_out, (uint32_t)n_ct);
   else if (rg.logN == 13)
     hipLaunchKernelGGL(k_encrypt_s<13>, grid_x, dim3(NttPlan<13>::NT), static_lds_bytes(13, 1), st, rg, pk->tab, rnd.u, m, rnd.e0, rnd.e1,
-                       ct_out, (uint32_t)n_ct, cts_per_slot);
+                       ct_out, (uint32_t)n_ct);
   else
     hipLaunchKernelGGL(k_encrypt, grid, dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 2), st, rg, pk->tab, rnd.u, m, rnd.e0, rnd.e1, ct_out);
   HIP_TRY(hipGetLastError());
@@ -1559,12 +1560,6 @@ he_status he_ctx_create(const he_params* params, int device, he_ctx** out) try {
   if (!ctx) return fail(HE_ERR_NOMEM, "host allocation failed");
   ctx->device = device;
   ctx->static_scratch = g_static_scratch[device];
-  if (hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) != hipSuccess ||   // default priority
-      hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming) != hipSuccess ||
-      hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming) != hipSuccess) {
-    he_ctx_destroy(ctx);
-    return fail(HE_ERR_HIP, "could not create the context's side stream");
-  }
   const uint32_t logN = params->log2_n, N = 1u << logN, n = N / 2, L = params->n_limbs;
   if (params->primes) {
     ctx->primes.assign(params->primes, params->primes + L);
@@ -1593,6 +1588,8 @@ he_status he_ctx_create(const he_params* params, int device, he_ctx** out) try {
     rg.q[j] = q;
     const he_host::U2 ni = he_host::shoup(he_host::invmod(N % q, q), q);
     rg.ninv[j] = make_uint2(ni.w, ni.wp);
+    const he_host::U2 niw = he_host::shoup((uint32_t)((uint64_t)ni.w * twi[(size_t)j * N + 1].x % q), q);
+    rg.ninv_w1[j] = make_uint2(niw.w, niw.wp);
     const uint32_t q_last = ctx->primes[L - 1];
     ctx->agg.q[j] = q;
     const he_host::U2 c32 = he_host::shoup((uint32_t)((1ull << 32) % q), q);
@@ -1699,9 +1696,6 @@ void he_ctx_destroy(he_ctx* ctx) {
     (void)hipEventDestroy(sp.stop);
   }
   for (hipEvent_t e : ctx->event_pool) (void)hipEventDestroy(e);
-  if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
-  if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
-  if (ctx->side) (void)hipStreamDestroy(ctx->side);
   delete ctx;
 }
 
@@ -2049,16 +2043,13 @@ static he_status encrypt_masked_impl(he_ctx* ctx, const he_pk* pk, const he_mask
     if (s != HE_OK) return s;
   }
   const EncScratch sc = carve_enc_scratch(fixed_scratch ? fixed_scratch : ctx->ws, chunk, N);
-  const bool beside = n_plain && n_ct;  // the copy of the remainder overlaps the transforms
-  hipStream_t pst = beside ? ctx->side : st;
+  // The remainder is compacted first, on the same stream: an HBM-bound copy beside the transform kernels (tried on a
+  // second stream, and on a disjoint set of compute units) lengthens them by as much as it saves, because it evicts
+  // their twiddle and key tables from L2.
   if (n_plain) {
-    if (beside) {
-      s = side_fork(ctx, st);
-      if (s != HE_OK) return s;
-    }
     {
-      KernelTimer timer_(ctx, KID_PLAIN_MOVE, pst);
-      launch_plain_move<false>(mk, w_dev, plain_out_dev, pst);
+      KernelTimer timer_(ctx, KID_PLAIN_MOVE, st);
+      launch_plain_move<false>(mk, w_dev, plain_out_dev, st);
       HIP_TRY(hipGetLastError());
     }
     if (pre_scale != 1.0) {  // weigh the compacted remainder in place: float32(alpha * x), product in float64
@@ -2066,7 +2057,7 @@ static he_status encrypt_masked_impl(he_ctx* ctx, const he_pk* pk, const he_mask
       pa.K = 1;
       pa.w[0] = plain_out_dev;
       pa.alpha[0] = pre_scale;
-      s = launch_plain(ctx, false, true, pa, n_plain, nullptr, nullptr, plain_out_dev, pst);
+      s = launch_plain(ctx, false, true, pa, n_plain, nullptr, nullptr, plain_out_dev, st);
       if (s != HE_OK) return s;
     }
   }
@@ -2077,7 +2068,6 @@ static he_status encrypt_masked_impl(he_ctx* ctx, const he_pk* pk, const he_mask
     s = launch_encrypt(ctx, pk, cn, sc.m, sc, ct_out_dev + c0 * 2 * rg.L * N, st);
     if (s != HE_OK) return s;
   }
-  if (beside) return side_join(ctx, st);
   return HE_OK;
 } catch (...) {
   return on_exception();
@@ -2263,15 +2253,9 @@ static he_status decrypt_merge_impl(he_ctx* ctx, const he_sk* sk, const he_mask*
     if (s != HE_OK) return s;
   }
   uint32_t* d = static_cast<uint32_t*>(ctx->ws);
-  const bool beside = n_plain && n_ct;  // the scatter of the remainder writes other entries than the decoder does
-  hipStream_t pst = beside ? ctx->side : st;
-  if (n_plain) {
-    if (beside) {
-      s = side_fork(ctx, st);
-      if (s != HE_OK) return s;
-    }
-    KernelTimer timer_(ctx, KID_PLAIN_MOVE, pst);
-    launch_plain_move<true>(mk, plain_glob_dev, w_out_dev, pst);
+  if (n_plain) {  // the scatter of the remainder writes other entries than the decoder does
+    KernelTimer timer_(ctx, KID_PLAIN_MOVE, st);
+    launch_plain_move<true>(mk, plain_glob_dev, w_out_dev, st);
     HIP_TRY(hipGetLastError());
   }
   for (uint64_t c0 = 0; c0 < n_ct; c0 += chunk) {
@@ -2281,7 +2265,6 @@ static he_status decrypt_merge_impl(he_ctx* ctx, const he_sk* sk, const he_mask*
     s = launch_decode(ctx, level, mk, d, c0, cn, w_out_dev, nullptr, st);
     if (s != HE_OK) return s;
   }
-  if (beside) return side_join(ctx, st);
   return HE_OK;
 } catch (...) {
   return on_exception();
@@ -2430,6 +2413,31 @@ he_status he_debug_count_out_of_range(he_ctx* ctx, const float* w_dev, uint64_t 
   hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, reinterpret_cast<uint32_t*>(cnt), (uint64_t)2, 0u);
   hipLaunchKernelGGL(k_count_out_of_range, dim3(grid_for(n, 256, 4096)), dim3(256), 0, st, w_dev, n,
                      std::ldexp(1.0, (int)ctx->ring.scale_bits), cnt);
+  HIP_TRY(hipGetLastError());
+  unsigned long long host = 0;
+  HIP_TRY(hipMemcpyAsync(&host, cnt, sizeof(host), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  *count_host = host;
+  return HE_OK;
+} catch (...) {
+  return on_exception();
+}
+
+he_status he_debug_count_noncanonical(he_ctx* ctx, const uint32_t* ct_dev, uint64_t n_ct, uint32_t level, uint64_t* count_host,
+                                      void* stream) try {
+  he_status s = check_ctx(ctx);
+  if (s != HE_OK) return s;
+  if (!count_host || (n_ct && !ct_dev)) return fail(HE_ERR_INVALID_ARG, "null argument");
+  if (level < 1 || level > ctx->ring.L) return fail(HE_ERR_LEVEL, "level must be in 1..L");
+  *count_host = 0;
+  if (n_ct == 0) return HE_OK;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  s = ensure_ws(ctx, 256);
+  if (s != HE_OK) return s;
+  unsigned long long* cnt = static_cast<unsigned long long*>(ctx->ws);
+  const uint64_t n_words = n_ct * 2 * level * ctx->ring.N;
+  hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, reinterpret_cast<uint32_t*>(cnt), (uint64_t)2, 0u);
+  hipLaunchKernelGGL(k_count_noncanonical, dim3(grid_for(n_words, 256, 8192)), dim3(256), 0, st, ctx->ring, ct_dev, n_words, level, cnt);
   HIP_TRY(hipGetLastError());
   unsigned long long host = 0;
   HIP_TRY(hipMemcpyAsync(&host, cnt, sizeof(host), hipMemcpyDeviceToHost, st));

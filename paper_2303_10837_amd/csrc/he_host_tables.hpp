@@ -123,13 +123,13 @@ struct D2 {
   double x, y;
 };
 
-// exp(sign * 2 pi i * num / den), evaluated in long double with the angle reduced to the
-// first octant so that the table is accurate to the last bit or so.
+// exp(2 pi i * num / den), den a power of two: the turn fraction num / den is exact, the angle and cosl / sinl are
+// evaluated in long double (64-bit mantissa) and rounded once to double, so an entry is off by at most about one unit
+// in the last place of a double.
 inline D2 unit_root(uint64_t num, uint64_t den) {
   const long double pi = 3.14159265358979323846264338327950288L;
   num %= den;
-  // exploit symmetries: angle = 2 pi num/den
-  long double frac = (long double)num / (long double)den;  // exact enough: den is a power of two
+  long double frac = (long double)num / (long double)den;  // exact: den is a power of two
   long double ang = 2.0L * pi * frac;
   return D2{(double)cosl(ang), (double)sinl(ang)};
 }

@@ -58,8 +58,14 @@ struct PassGeom {
 // every element whose index has the next stage's pairing bit set (both outputs of a butterfly
 // share that bit); after the last stage of a pass only when the caller says so (LAZY_LAST: the
 // pass is followed by a pointwise key product).  Such a butterfly costs 8 instructions, not 11.
-template <int LOGN, int S0, int R, bool INV, int NP, bool LAZY_LAST = false>
-__device__ __forceinline__ void bfly_stages(uint32_t (&v)[NP][1 << R], int b, const uint2* __restrict__ tw, uint32_t q) {
+//
+// SCALE_LAST (inverse, pass 0 only): the factor 1/N of a standalone inverse transform rides on the last stage, whose
+// twiddle is then psi^-bitrev(1) / N and whose sum output takes a Shoup product by 1/N in place of its conditional
+// subtraction (13 instructions for that butterfly instead of 10 and a separate product on both outputs).
+template <int LOGN, int S0, int R, bool INV, int NP, bool LAZY_LAST = false, bool SCALE_LAST = false>
+__device__ __forceinline__ void bfly_stages(uint32_t (&v)[NP][1 << R], int b, const uint2* __restrict__ tw, uint32_t q,
+                                            uint2 n_inv = uint2{0, 0}, uint2 w1_n_inv = uint2{0, 0}) {
+  static_assert(!SCALE_LAST || (INV && S0 == 0), "the scaled last stage is stage 0 of the inverse");
   using G = PassGeom<LOGN, S0, R>;
   constexpr int E = 1 << R;
   const int bb = (S0 == 0) ? 0 : (G::UNIFORM ? __builtin_amdgcn_readfirstlane(b) : b);
@@ -96,11 +102,12 @@ __device__ __forceinline__ void bfly_stages(uint32_t (&v)[NP][1 << R], int b, co
 #pragma unroll
       for (int i = 0; i < E; ++i) {
         if (i & half) continue;
-        const uint2 w = twk[i >> (R - k)];
+        const uint2 w = (SCALE_LAST && k == 0) ? w1_n_inv : twk[i >> (R - k)];
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
           const uint32_t x = v[p][i], y = v[p][i + half];
-          v[p][i] = add_mod(x, y, q);
+          if (SCALE_LAST && k == 0) v[p][i] = mul_shoup_mad<true>(x + y, n_inv, q);  // x + y < 2q: any 32-bit value is fine
+          else v[p][i] = add_mod(x, y, q);
           v[p][i + half] = mul_shoup_mad<WS>(x - y + q, w, q);
         }
       }

@@ -538,3 +538,24 @@ def test_three_training_rounds(he):
     assert np.abs(err[enc_idx]).max() < 16 * sigma * np.sqrt(3)
     assert 0.6 * sigma < err[enc_idx].std() < 1.4 * sigma * np.sqrt(3)
     mask.close()
+
+
+def test_noncanonical_residue_count(he):
+    """he_debug_count_noncanonical counts exactly the words that are not below their limb's prime, at both levels."""
+    ctx, keys, p, _ = _setup(he, 10, 3)
+    rs = np.random.default_rng(13)
+    for level in (3, 2):
+        ct = np.stack([rs.integers(0, q, (5, 2, p.N)) for q in p.primes[:level]], axis=2).astype(np.int64)
+        assert he.he_debug_count_noncanonical(ctx, _dev(ct, torch.int32), level) == 0
+        bad = ct.copy()
+        bad[0, 0, 0, 0] = p.primes[0]                    # q itself
+        bad[4, 1, level - 1, p.N - 1] = 2 ** 32 - 1      # the largest word
+        bad[2, 1, 1, 7] = p.primes[1] + 5
+        bad[3, 0, 1, 9] = p.primes[1] - 1                # still canonical
+        as_i32 = torch.from_numpy(bad.astype(np.uint32).view(np.int32)).cuda()
+        assert he.he_debug_count_noncanonical(ctx, as_i32, level) == 3
+    # what the library itself produces is canonical
+    mask = he.he_mask_create(ctx, 3 * p.n_slots, [0], [3 * p.n_slots])
+    ct, _ = he.he_encrypt_masked(ctx, keys, mask, SEED, 0, _dev(rs.normal(0, 0.05, 3 * p.n_slots).astype(np.float32)))
+    assert he.he_debug_count_noncanonical(ctx, ct, 3) == 0
+    assert he.he_debug_count_noncanonical(ctx, torch.empty((0, 2, 3, p.N), dtype=torch.int32, device="cuda"), 3) == 0
