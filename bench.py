@@ -78,6 +78,38 @@ def measured_valu_busy(workload):
     return out
 
 
+def measured_wave_instructions(workload):
+    """Vector-ALU wave instructions per launch (rocprofv3 SQ_INSTS_VALU) per kernel from the committed summary, if any."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"alu_counters_{workload}.txt")
+    out = {}
+    if os.path.exists(path):
+        for line in open(path):
+            parts = line.split()
+            if len(parts) >= 4 and parts[0] == "valu_wave_instructions_per_launch":
+                out[parts[1]] = (float(parts[2]), float(parts[3]))      # (instructions, ciphertexts in that launch)
+    return out
+
+
+def issue_rates():
+    """Runs the register-only instruction-rate loops of libhe_issue_rates.so (include/he_issue_rates.h)."""
+    import ctypes as C
+    from paper_2303_10837_amd import build
+    lib = C.CDLL(build.RATES_LIB_PATH)
+    lib.he_issue_rates_name.restype = C.c_char_p
+    n = lib.he_issue_rates_count()
+    ns, n_simd = (C.c_double * n)(), C.c_uint32(0)
+    rc = lib.he_issue_rates_run(0, ns, C.byref(n_simd))
+    if rc != 0:
+        raise RuntimeError(f"he_issue_rates_run: hip error {rc}")
+    rows = []
+    for i in range(n):
+        k = lib.he_issue_rates_instructions(i)
+        rows.append({"what": lib.he_issue_rates_name(i).decode(), "instructions": k, "ns_per_simd": ns[i],
+                     "cycles_at_2.4GHz": ns[i] * 2.4, "cycles_per_instruction": ns[i] * 2.4 / k,
+                     "chip_lane_TOPs": k * 64 * n_simd.value / ns[i] / 1e3})
+    return {"n_simd": n_simd.value, "waves_per_simd": 8, "rows": rows}
+
+
 def _oracle_ciphertext_job(job):
     """One ciphertext index of the round on the CPU oracle: every client's encode + encrypt, the server's weighted sum
     and rescale (or plain sum), decrypt, lift, decode.  Runs in the parent (one core) and in spawned worker processes
@@ -477,6 +509,16 @@ def run_workload(he, si, torch, name, args, steps, warmup, headline):
             "encode_cts_per_s": n_ct * K * steps / (ec_ms * 1e-3) if ec_ms else 0.0,
             "decode_cts_per_s": n_ct * steps / (dc_ms * 1e-3) if dc_ms else 0.0,
             "decrypt_cts_per_s": n_ct * steps / (dq_ms * 1e-3) if dq_ms else 0.0}
+    # ALU rooflines of the encoder (Philox sampler + fp64 FFT), the decryption kernel and the decoder (exact lift + FFT):
+    # executed vector instructions per ciphertext from the committed rocprofv3 SQ_INSTS_VALU summary x 64 lanes x the
+    # ciphertext rate measured here, against the same one-instruction-per-4-cycles peak
+    wi = measured_wave_instructions(w.name)
+    for kname, rate in (("k_encode_r", side["encode_cts_per_s"]), ("k_decrypt_s", side["decrypt_cts_per_s"]), ("k_decode_h", side["decode_cts_per_s"])):
+        if kname in wi and wi[kname][1]:
+            per_ct = wi[kname][0] / wi[kname][1]
+            tops = per_ct * 64 * rate / 1e12
+            side["roofline_" + kname] = {"bound": "alu", "achieved": tops, "peak": ALU_PEAK_TOPS, "unit": "TOP/s", "frac": tops / ALU_PEAK_TOPS,
+                                         "wave_instructions_per_ciphertext_profiled": per_ct}
 
     phase_bytes = [K * (4 * P_enc + 8 * n_pl + n_ct * 8 * L * N),                       # parameters read, remainder copied, ciphertexts written
                    n_ct * 8 * N * (K * L + L_out) + n_pl * (4 * K + 4),               # K ciphertexts and remainders read, one of each written
@@ -522,6 +564,8 @@ def run_workload(he, si, torch, name, args, steps, warmup, headline):
             res["crypto_param_sweep"] = crypto_param_sweep(he, torch)
         if args.select_bench:
             res["mask_select"] = mask_select_bench(he, ctx, torch)
+        if args.issue_rates:
+            res["issue_rates"] = issue_rates()
         if not args.no_cpu_baseline:
             from oracle import fedavg as ofed                                  # host index arithmetic of the gather only
             n = N // 2
@@ -596,6 +640,8 @@ def main():
                     help="also time the encryption-mask selection (top-p of a sensitivity map) on 25.6M / 110M / 1.3B entries")
     ap.add_argument("--k-sweep", action="store_true",
                     help="also time he_aggregate alone for K = 3 ... 200 clients (server cost against the number of clients)")
+    ap.add_argument("--issue-rates", action="store_true",
+                    help="also run the register-only instruction-rate loops behind the integer-ALU peak (libhe_issue_rates.so)")
     ap.add_argument("--stream-clients", action="store_true",
                     help="fold each client's plaintext remainder into the server's accumulator right after its encryption "
                          "(he_aggregate_begin/add/finalize) and keep only 4 distinct client vectors resident; chosen by "

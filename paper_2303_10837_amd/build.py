@@ -8,6 +8,9 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 REPO_DIR = os.path.dirname(PKG_DIR)
 LIB_PATH = os.path.join(PKG_DIR, "libhe_fedavg.so")
 SOURCES = [os.path.join(PKG_DIR, "csrc", "he_fedavg.hip")]
+# measurement helper of bench.py --issue-rates (register-only instruction-rate loops): a library of its own
+RATES_LIB_PATH = os.path.join(PKG_DIR, "libhe_issue_rates.so")
+RATES_SOURCES = [os.path.join(PKG_DIR, "csrc", "he_issue_rates.hip")]
 
 
 def hipcc_path() -> str:
@@ -18,6 +21,12 @@ def hipcc_path() -> str:
 
 
 def build_library(verbose: bool = False) -> str:
+    _compile(LIB_PATH, SOURCES, verbose)
+    _compile(RATES_LIB_PATH, RATES_SOURCES, verbose)
+    return LIB_PATH
+
+
+def _compile(lib_path, sources, verbose):
     cmd = [
         hipcc_path(), "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
         # No packed-fp32 code generation on the device (checked on the ISA: a float2 multiply-add compiles to v_pk_fma_f32
@@ -26,7 +35,7 @@ def build_library(verbose: bool = False) -> str:
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
         "-Wall", "-Wno-unused-function",
         "-I", os.path.join(REPO_DIR, "include"), "-I", os.path.join(PKG_DIR, "csrc"),
-        "-o", LIB_PATH, *SOURCES,
+        "-o", lib_path, *sources,
     ]
     if verbose:
         print(" ".join(cmd), flush=True)
@@ -37,7 +46,6 @@ def build_library(verbose: bool = False) -> str:
     rest = "\n".join(l for l in res.stderr.splitlines() if l.strip() and l.strip() != noise)
     if verbose and rest:
         print(rest)
-    return LIB_PATH
 
 
 if __name__ == "__main__":

@@ -27,6 +27,20 @@ def test_header_symbols_are_exported_and_bound():
     assert declared == set(binding.EXPORTED_SYMBOLS)
 
 
+def test_issue_rate_library_exports_its_header():
+    from paper_2303_10837_amd import build
+    _lib_path()
+    if not os.path.exists(build.RATES_LIB_PATH):
+        build.build_library()
+    text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "he_issue_rates.h")).read(), flags=re.S)
+    declared = set(re.findall(r"\b(he_issue_rates[a-z0-9_]*)\s*\(", text))
+    assert declared == {"he_issue_rates_count", "he_issue_rates_name", "he_issue_rates_instructions", "he_issue_rates_run"}
+    lib = ctypes.CDLL(build.RATES_LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name)
+    assert lib.he_issue_rates_count() >= 10       # host-side table only: no GPU call
+
+
 def test_no_cpu_fallback_when_library_is_missing(monkeypatch, tmp_path):
     from paper_2303_10837_amd import binding
     monkeypatch.setattr(binding, "_LIB", None)
