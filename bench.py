@@ -122,10 +122,10 @@ def _oracle_ciphertext_job(job):
     if keys is None:
         keys = _ORACLE_KEYS.setdefault((params, seed), osch.keygen(p, seed))
     if client_weighted:
-        cts = [osch.encrypt(p, keys, oenc.encode_fft(np.float64(a) * z, p.log2_n, p.scale_bits), seed, i, c)
+        cts = [osch.encrypt(p, keys, oenc.encode_fft(np.float64(a) * z, p.log2_n, p.scale_bits), seed + 1, i, c)
                for i, (z, a) in enumerate(zip(slots, alpha))]
         return ofed.decode_ct_level(p, keys, osch.sum_ciphertexts(p, cts), p.n_limbs)[:1]
-    cts = [osch.encrypt(p, keys, oenc.encode_fft(z, p.log2_n, p.scale_bits), seed, i, c) for i, z in enumerate(slots)]
+    cts = [osch.encrypt(p, keys, oenc.encode_fft(z, p.log2_n, p.scale_bits), seed + 1, i, c) for i, z in enumerate(slots)]   # round seed != key seed
     return ofed.decode_ct(p, keys, osch.aggregate(p, cts, alpha))[:1]
 
 
@@ -324,8 +324,15 @@ def run_workload(he, si, torch, name, args, steps, warmup, headline):
         torch.cuda.synchronize()
     ev = [None] * 4
     phase_ms = np.zeros(3)
+    # encryption randomness: a fresh seed for every round (step), unrelated to the key generation seed; never reused with a client id
+    round_seed = [(w.seed << 20) ^ 0x5EED]
+
+    def next_round_seed():
+        round_seed[0] += 1
+        return round_seed[0]
 
     def step_streamed(record):
+        seed_t = next_round_seed()
         cur = torch.cuda.current_stream()
         if record:
             ev[0].record()
@@ -341,7 +348,7 @@ def run_workload(he, si, torch, name, args, steps, warmup, headline):
                 cur.wait_event(folded[half])
             slots = [half * G + (i - g0) for i in grp]
             for i, sl in zip(grp, slots):
-                he.he_encrypt_masked(ctx, keys, mask, w.seed, i, ws[i], cts[i], plains[sl % len(plains)])
+                he.he_encrypt_masked(ctx, keys, mask, seed_t, i, ws[i], cts[i], plains[sl % len(plains)])
             if n_pl:
                 sent = torch.cuda.Event()
                 sent.record(cur)
@@ -374,6 +381,7 @@ def run_workload(he, si, torch, name, args, steps, warmup, headline):
     torch.cuda.synchronize()
 
     def step_resident(record):
+        seed_t = next_round_seed()
         cur = torch.cuda.current_stream()
         if record:
             ev[0].record()
@@ -383,9 +391,9 @@ def run_workload(he, si, torch, name, args, steps, warmup, headline):
             c_i, k_i, m_i, st = lanes[i % S]
             with torch.cuda.stream(st if st is not None else cur):
                 if client_weighted:
-                    he.he_encrypt_masked_weighted(c_i, k_i, m_i, w.seed, i, alpha[i], ws[i], cts[i], plains[i])
+                    he.he_encrypt_masked_weighted(c_i, k_i, m_i, seed_t, i, alpha[i], ws[i], cts[i], plains[i])
                 else:
-                    he.he_encrypt_masked(c_i, k_i, m_i, w.seed, i, ws[i], cts[i], plains[i])
+                    he.he_encrypt_masked(c_i, k_i, m_i, seed_t, i, ws[i], cts[i], plains[i])
         for _, _, _, st in lanes[1:]:
             cur.wait_stream(st)
         if record:
