@@ -1,7 +1,6 @@
 """A whole round captured in a HIP graph replays to the bytes of the eager round.
 
-The library's calls only enqueue work on the given stream (plus the context's own side stream, forked from and
-joined back into it), allocate nothing once the context's scratch has grown to the workload's size in a first eager
+The library's calls only enqueue work on the given stream, allocate nothing once the context's scratch has grown to the workload's size in a first eager
 call, and clear memory with kernels, not memset nodes: so a round can be captured and replayed.  Every replay is
 checked, with eager work and synchronisations of the same context in between.
 """
@@ -21,7 +20,7 @@ def test_graph_replay_matches_eager(log2_n, limbs):
     keys = he.he_keygen(ctx, 99)
     n = ctx.n_slots
     P = 6 * n + 321
-    runs = [(5, 2 * n + 7), (3 * n, n), (5 * n + 11, 300)]            # selective: the remainder runs on the side stream
+    runs = [(5, 2 * n + 7), (3 * n, n), (5 * n + 11, 300)]            # selective: a plaintext remainder is compacted and scattered too
     mask = he.he_mask_create(ctx, P, [r[0] for r in runs], [r[1] for r in runs])
     K = 3
     rs = np.random.default_rng(0)
