@@ -248,7 +248,7 @@ def crypto_param_sweep(he, torch, P=1_663_370, K=3, reps=3):
 
 def mask_select_bench(he, ctx, torch, sizes=(25_600_000, 110_000_000, 1_300_000_000), ratio=0.1, reps=3):
     """Select(global privacy map, p) on model-sized maps (layer-structured synthetic sensitivities): wall time of the
-    whole set-up call (three histogram passes, mark, run extraction, temporaries, the run list's trip to the host)."""
+    whole set-up call (three histogram passes, mark, the mask object's tables built on the device, temporaries)."""
     rows = []
     for P in sizes:
         g = torch.Generator(device="cuda").manual_seed(P % 1000)

@@ -1181,7 +1181,10 @@ struct he_mask {
   he_ctx* ctx;
   MaskDev dev{};
   void* dev_block = nullptr;
-  std::vector<uint64_t> starts, lens;  // host copy of the run list
+  uint64_t n_runs = 0;
+  // host copy of the run list; masks built on the device (he_mask_from_bytes, he_mask_select_top) fetch it on first use
+  mutable std::vector<uint64_t> starts, lens;
+  mutable bool host_runs_valid = true;
 };
 
 namespace {
@@ -1821,6 +1824,7 @@ he_status he_mask_create(he_ctx* ctx, uint64_t P, const uint64_t* starts, const 
   try {  // the host copy of the run list is the last thing that can throw
     mk->starts.assign(starts, starts + n_runs);
     mk->lens.assign(lens, lens + n_runs);
+    mk->n_runs = n_runs;
   } catch (...) {
     he_mask_destroy(mk);
     return on_exception();
@@ -1850,20 +1854,22 @@ he_status he_mask_create(he_ctx* ctx, uint64_t P, const uint64_t* starts, const 
   return on_exception();
 }
 
-// Run list of a device byte mask (non-zero = selected), extracted on the GPU: per-chunk counts of
-// run starts and ends, an exclusive scan, an emit pass; only the runs themselves travel to the host.
+// Mask object of a device byte mask (non-zero = selected), built on the GPU: per-chunk counts of run starts, run ends
+// and set bytes, three exclusive scans, and an emit pass that writes the object's device tables (masked and complement
+// runs with their packed offsets) in place.  Only five words travel to the host; the run list itself follows when
+// he_mask_runs asks for it.
 static he_status mask_from_device_bytes(he_ctx* ctx, uint64_t P, const uint8_t* mask_dev, he_mask** out, hipStream_t st) try {
   using namespace he_sel;
   if (P == 0) return he_mask_create(ctx, 0, nullptr, nullptr, 0, out);
   const uint64_t n_chunks = (P + kChunk - 1) / kChunk;
   if (n_chunks > 0x7FFFFFFFull) return fail(HE_ERR_INVALID_ARG, "vector too long");
   char* tmp = nullptr;
-  uint64_t* runs_dev = nullptr;
+  he_mask* mk = nullptr;
   const size_t cnt_bytes = ((n_chunks * sizeof(uint32_t) + 255) / 256) * 256;
   const size_t off_bytes = (((n_chunks + 1) * sizeof(uint64_t) + 255) / 256) * 256;
   auto cleanup = [&]() {
     if (tmp) (void)hipFree(tmp);
-    if (runs_dev) (void)hipFree(runs_dev);
+    he_mask_destroy(mk);
   };
 #define MK_TRY(expr)                                                                 \
   do {                                                                               \
@@ -1873,46 +1879,74 @@ static he_status mask_from_device_bytes(he_ctx* ctx, uint64_t P, const uint8_t* 
       return fail(e_ == hipErrorOutOfMemory ? HE_ERR_NOMEM : HE_ERR_HIP, std::string(#expr) + ": " + hipGetErrorString(e_)); \
     }                                                                                \
   } while (0)
-  MK_TRY(hipMalloc(&tmp, 2 * cnt_bytes + 2 * off_bytes));
+  MK_TRY(hipMalloc(&tmp, 3 * cnt_bytes + 3 * off_bytes));
   uint32_t* n_start = reinterpret_cast<uint32_t*>(tmp);
   uint32_t* n_end = reinterpret_cast<uint32_t*>(tmp + cnt_bytes);
-  uint64_t* off_start = reinterpret_cast<uint64_t*>(tmp + 2 * cnt_bytes);
-  uint64_t* off_end = reinterpret_cast<uint64_t*>(tmp + 2 * cnt_bytes + off_bytes);
-  hipLaunchKernelGGL(k_runs<false>, dim3((uint32_t)n_chunks), dim3(kThreads), 0, st, mask_dev, P, n_start, n_end, nullptr, nullptr,
-                     nullptr, nullptr);
-  hipLaunchKernelGGL(k_scan_counts, dim3(1), dim3(1024), 0, st, n_start, n_chunks, off_start);
-  hipLaunchKernelGGL(k_scan_counts, dim3(1), dim3(1024), 0, st, n_end, n_chunks, off_end);
+  uint32_t* n_set = reinterpret_cast<uint32_t*>(tmp + 2 * cnt_bytes);
+  uint64_t* off_start = reinterpret_cast<uint64_t*>(tmp + 3 * cnt_bytes);
+  uint64_t* off_end = reinterpret_cast<uint64_t*>(tmp + 3 * cnt_bytes + off_bytes);
+  uint64_t* off_set = reinterpret_cast<uint64_t*>(tmp + 3 * cnt_bytes + 2 * off_bytes);
+  hipLaunchKernelGGL(k_runs<false>, dim3((uint32_t)n_chunks), dim3(kThreads), 0, st, mask_dev, P, n_start, n_end, n_set, nullptr, nullptr,
+                     nullptr, nullptr, nullptr, nullptr, nullptr);
+  hipLaunchKernelGGL(k_scan_counts, dim3(3), dim3(1024), 0, st, n_start, n_chunks, off_start, (uint64_t)(cnt_bytes / sizeof(uint32_t)),
+                     (uint64_t)(off_bytes / sizeof(uint64_t)));  // the three arrays, one workgroup each
   MK_TRY(hipGetLastError());
-  uint64_t totals[2] = {0, 0};
+  uint64_t totals[3] = {0, 0, 0};
+  uint8_t edge[2] = {0, 0};  // first and last byte of the mask
   MK_TRY(hipMemcpyAsync(&totals[0], off_start + n_chunks, sizeof(uint64_t), hipMemcpyDeviceToHost, st));
   MK_TRY(hipMemcpyAsync(&totals[1], off_end + n_chunks, sizeof(uint64_t), hipMemcpyDeviceToHost, st));
+  MK_TRY(hipMemcpyAsync(&totals[2], off_set + n_chunks, sizeof(uint64_t), hipMemcpyDeviceToHost, st));
+  MK_TRY(hipMemcpyAsync(&edge[0], mask_dev, 1, hipMemcpyDeviceToHost, st));
+  MK_TRY(hipMemcpyAsync(&edge[1], mask_dev + (P - 1), 1, hipMemcpyDeviceToHost, st));
   MK_TRY(hipStreamSynchronize(st));
-  const uint64_t R = totals[0];
-  if (totals[1] != R) {
+  const uint64_t R = totals[0], P_enc = totals[2];
+  if (totals[1] != R || P_enc > P) {
     cleanup();
     return fail(HE_ERR_HIP, "run extraction: starts and ends disagree");
   }
-  std::vector<uint64_t> starts, lens;
-  try {
-    starts.resize(R);
-    lens.resize(R);
-  } catch (...) {
+  if (R == 0) {
     cleanup();
-    return on_exception();
+    return he_mask_create(ctx, P, nullptr, nullptr, 0, out);
   }
-  if (R) {
-    MK_TRY(hipMalloc(&runs_dev, 2 * R * sizeof(uint64_t)));
-    hipLaunchKernelGGL(k_runs<true>, dim3((uint32_t)n_chunks), dim3(kThreads), 0, st, mask_dev, P, nullptr, nullptr, off_start, off_end,
-                       runs_dev, runs_dev + R);
-    MK_TRY(hipGetLastError());
-    MK_TRY(hipMemcpyAsync(starts.data(), runs_dev, R * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
-    MK_TRY(hipMemcpyAsync(lens.data(), runs_dev + R, R * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
-    MK_TRY(hipStreamSynchronize(st));
-    for (uint64_t r = 0; r < R; ++r) lens[r] -= starts[r];  // ends -> lengths
+  if (R >= (1ull << 31)) {
+    cleanup();
+    return fail(HE_ERR_INVALID_ARG, "too many runs");
   }
-  cleanup();
+  const uint64_t n_cruns = R + 1 - (edge[0] ? 1 : 0) - (edge[1] ? 1 : 0);
+  mk = new (std::nothrow) he_mask();
+  if (!mk) {
+    cleanup();
+    return fail(HE_ERR_NOMEM, "host allocation failed");
+  }
+  mk->ctx = ctx;
+  mk->n_runs = R;
+  mk->host_runs_valid = false;
+  // same layout as he_mask_create: start | prefix | cstart | cprefix, one spare word after start and cstart
+  const size_t o_st = 0, o_pf = o_st + R + 1, o_cs = o_pf + R + 1, o_cp = o_cs + n_cruns + 1, n_words = o_cp + n_cruns + 1;
+  MK_TRY(hipMalloc(&mk->dev_block, n_words * sizeof(uint64_t)));
+  uint64_t* base = static_cast<uint64_t*>(mk->dev_block);
+  hipLaunchKernelGGL(k_runs<true>, dim3((uint32_t)n_chunks), dim3(kThreads), 0, st, mask_dev, P, nullptr, nullptr, nullptr, off_start, off_end,
+                     off_set, base + o_st, base + o_pf, base + o_cs, base + o_cp);
+  MK_TRY(hipGetLastError());
+  const uint64_t tail[3] = {P_enc, P - P_enc, 0};  // prefix[R] and cprefix[n_cruns]: the totals; the spare words: 0
+  MK_TRY(hipMemcpyAsync(base + o_pf + R, &tail[0], sizeof(uint64_t), hipMemcpyHostToDevice, st));
+  MK_TRY(hipMemcpyAsync(base + o_cp + n_cruns, &tail[1], sizeof(uint64_t), hipMemcpyHostToDevice, st));
+  MK_TRY(hipMemcpyAsync(base + o_st + R, &tail[2], sizeof(uint64_t), hipMemcpyHostToDevice, st));
+  MK_TRY(hipMemcpyAsync(base + o_cs + n_cruns, &tail[2], sizeof(uint64_t), hipMemcpyHostToDevice, st));
+  MK_TRY(hipStreamSynchronize(st));  // tmp is freed below, and tail[] leaves scope
+  (void)hipFree(tmp);
+  tmp = nullptr;
 #undef MK_TRY
-  return he_mask_create(ctx, P, starts.data(), lens.data(), R, out);
+  mk->dev.start = base + o_st;
+  mk->dev.prefix = base + o_pf;
+  mk->dev.cstart = base + o_cs;
+  mk->dev.cprefix = base + o_cp;
+  mk->dev.n_runs = (uint32_t)R;
+  mk->dev.n_cruns = (uint32_t)n_cruns;
+  mk->dev.P = P;
+  mk->dev.P_enc = P_enc;
+  *out = mk;
+  return HE_OK;
 } catch (...) {
   return on_exception();
 }
@@ -1978,7 +2012,7 @@ he_status he_mask_select_top(he_ctx* ctx, uint64_t P, const float* s_dev, double
   const bool rank_ties = fin.k_rem < fin.cnt_eq;  // only some of the elements equal to the threshold are taken
   if (rank_ties) {
     hipLaunchKernelGGL(k_count_eq, dim3((uint32_t)n_chunks), dim3(kThreads), 0, st, s_dev, P, state, eq_count);
-    hipLaunchKernelGGL(k_scan_counts, dim3(1), dim3(1024), 0, st, eq_count, n_chunks, eq_off);
+    hipLaunchKernelGGL(k_scan_counts, dim3(1), dim3(1024), 0, st, eq_count, n_chunks, eq_off, (uint64_t)0, (uint64_t)0);
   }
   hipLaunchKernelGGL(k_mark, dim3((uint32_t)n_chunks), dim3(kThreads), 0, st, s_dev, P, state, rank_ties ? eq_off : nullptr, mask_dev);
   SEL_TRY(hipGetLastError());
@@ -1996,10 +2030,21 @@ void he_mask_destroy(he_mask* mask) {
   delete mask;
 }
 
-uint64_t he_mask_n_runs(const he_mask* mask) { return mask ? mask->starts.size() : 0; }
+uint64_t he_mask_n_runs(const he_mask* mask) { return mask ? mask->n_runs : 0; }
 
 he_status he_mask_runs(const he_mask* mask, uint64_t* starts_host, uint64_t* lens_host) try {
-  if (!mask || ((!starts_host || !lens_host) && !mask->starts.empty())) return fail(HE_ERR_INVALID_ARG, "null argument");
+  if (!mask || ((!starts_host || !lens_host) && mask->n_runs)) return fail(HE_ERR_INVALID_ARG, "null argument");
+  if (!mask->host_runs_valid) {  // built on the device: fetch the run list now (synchronous), lengths from the packed offsets
+    const uint64_t R = mask->n_runs;
+    HIP_TRY(hipSetDevice(mask->ctx->device));
+    mask->starts.resize(R);
+    mask->lens.resize(R + 1);
+    HIP_TRY(hipMemcpy(mask->starts.data(), mask->dev.start, R * sizeof(uint64_t), hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(mask->lens.data(), mask->dev.prefix, (R + 1) * sizeof(uint64_t), hipMemcpyDeviceToHost));
+    for (uint64_t r = 0; r < R; ++r) mask->lens[r] = mask->lens[r + 1] - mask->lens[r];
+    mask->lens.resize(R);
+    mask->host_runs_valid = true;
+  }
   std::copy(mask->starts.begin(), mask->starts.end(), starts_host);
   std::copy(mask->lens.begin(), mask->lens.end(), lens_host);
   return HE_OK;

@@ -73,6 +73,29 @@ def test_mask_from_bytes_run_extraction(he, ctx):
     assert _runs(he, mask) == osel.runs_of(m != 0) == [(0, 8), (2040, 16), (4095, 2), (6143, 1)]
 
 
+def test_unaligned_vectors(he, ctx):
+    """Vectors that start at an odd element of an allocation (4-byte and 1-byte aligned only): the kernels' wide
+    loads and stores do not apply, the results are the same."""
+    rs = np.random.default_rng(8)
+    P = 5 * 2048 + 77
+    sens = np.abs(rs.normal(0, 1, P + 3)).astype(np.float32)
+    sens[rs.integers(0, P, 400)] = sens[17]                      # ties at some values
+    d = torch.from_numpy(sens).cuda()
+    for off in (1, 2, 3):
+        view = d[off:off + P]
+        assert view.data_ptr() % 16 == 4 * off
+        for ratio in (0.1, 0.5):
+            mask = he.he_mask_select_top(ctx, view, ratio)
+            assert _runs(he, mask) == osel.runs_of(osel.select_top(sens[off:off + P], ratio))
+            mask.close()
+    m = (rs.random(P + 7) < 0.4).astype(np.uint8)
+    dm = torch.from_numpy(m).cuda()
+    for off in (1, 3, 4, 7):
+        mask = he.he_mask_from_bytes(ctx, dm[off:off + P])
+        assert _runs(he, mask) == osel.runs_of(m[off:off + P] != 0)
+        mask.close()
+
+
 def test_select_large_vector_properties(he, ctx):
     """25.6M entries (the ResNet-50-sized workload), layer-structured sensitivities: the selection has exactly k
     entries, every selected value is >= every unselected one, and sampled windows match the oracle's definition."""
