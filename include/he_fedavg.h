@@ -123,9 +123,10 @@ void he_sk_destroy(he_sk* sk);
    n_runs = 0 is the empty mask (everything stays plaintext).  Synchronous. */
 he_status he_mask_create(he_ctx* ctx, uint64_t P, const uint64_t* starts_host,
                          const uint64_t* lens_host, uint64_t n_runs, he_mask** out);
-/* Builds the run list from a device byte mask (non-zero = encrypted).  The runs are
-   extracted on the GPU; only the run list travels to the host (set-up path, synchronous on
-   `stream`, allocates temporaries). */
+/* Builds the mask from a device byte mask (non-zero = encrypted).  The mask object's device
+   tables are written on the GPU and a handful of words travel to the host (set-up path,
+   synchronous on `stream`, allocates temporaries of about 36 bytes per 2048 entries).  Any
+   alignment of mask_dev is accepted; 8-byte alignment is faster. */
 he_status he_mask_from_bytes(he_ctx* ctx, uint64_t P, const uint8_t* mask_dev, he_mask** out,
                              void* stream);
 /* Select(global privacy map, p) of Algorithm 1 ("Server Encryption Mask Aggregation"; Section
@@ -133,11 +134,14 @@ he_status he_mask_from_bytes(he_ctx* ctx, uint64_t P, const uint8_t* mask_dev, h
    sensitive ones, that gets encrypted).  s_dev float32[P] is the aggregated sensitivity map (decrypted:
    the selection itself is not homomorphic); the mask takes the k = rint(ratio * P) largest
    entries (ties to even in k; equal sensitivities go to the lower parameter index; -0 = +0;
-   entries must not be NaN).  Radix select and run extraction on the GPU (set-up path,
-   synchronous on `stream`, allocates temporaries of about P + 24 KiB bytes). */
+   entries must not be NaN).  Radix select and the mask object's tables on the GPU (set-up path,
+   synchronous on `stream`, allocates temporaries of about P + 48 KiB bytes).  Any 4-byte
+   alignment of s_dev is accepted; 16-byte alignment is faster. */
 he_status he_mask_select_top(he_ctx* ctx, uint64_t P, const float* s_dev, double ratio,
                              he_mask** out, void* stream);
-/* Copies the run list to the host: starts_host / lens_host hold he_mask_n_runs entries. */
+/* Copies the run list to the host: starts_host / lens_host hold he_mask_n_runs entries.
+   For a mask built on the GPU (the two calls above) the first he_mask_runs fetches the list from
+   the device with a blocking copy; he_mask_runs on one mask is not safe from several threads. */
 uint64_t he_mask_n_runs(const he_mask* mask);
 he_status he_mask_runs(const he_mask* mask, uint64_t* starts_host, uint64_t* lens_host);
 void he_mask_destroy(he_mask* mask);
