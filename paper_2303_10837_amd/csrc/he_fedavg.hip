@@ -2063,7 +2063,7 @@ uint64_t he_n_ct(const he_ctx* ctx, const he_mask* mask) {
 // ---- client: encrypt -------------------------------------------------------------------
 
 // fixed_scratch: when given (he_encrypt_masked_static), the per-ciphertext scratch lives there and the call
-// allocates nothing; it must then hold all n_ct ciphertexts' scratch at once.
+// allocates nothing; the call is refused unless that block holds the scratch of all n_ct ciphertexts.
 static he_status encrypt_masked_impl(he_ctx* ctx, const he_pk* pk, const he_mask* mask, uint64_t seed, uint32_t client_id,
                                      double pre_scale, const float* w_dev, uint32_t* ct_out_dev, float* plain_out_dev,
                                      void* stream, void* fixed_scratch = nullptr, size_t fixed_bytes = 0) try {
@@ -2082,7 +2082,6 @@ static he_status encrypt_masked_impl(he_ctx* ctx, const he_pk* pk, const he_mask
   if (fixed_scratch) {
     if (n_ct * N * kEncScratchBytesPerCoeff > fixed_bytes)
       return fail(HE_ERR_INVALID_ARG, "too many ciphertexts for the static scratch: n_ct * N * 7 bytes must not exceed HE_STATIC_SCRATCH_BYTES");
-    chunk = n_ct;
   } else if (chunk) {
     s = ensure_ws(ctx, chunk * N * kEncScratchBytesPerCoeff);
     if (s != HE_OK) return s;
