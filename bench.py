@@ -322,7 +322,8 @@ def run_workload(he, si, torch, name, args, steps, warmup, headline, copy_gbs=No
     out = torch.empty((w.n_params,), dtype=torch.float32, device="cuda")
     # The server is its own party with its own copy of the public crypto context (it never holds a key).  In the
     # streamed form it works on a second stream and folds the plaintext remainders of G clients at a time into its
-    # float64 accumulator (one read-modify-write of the accumulator per G clients).  With one set of G buffers the
+    # float64 accumulator (one read-modify-write of the accumulator per G clients; the first fold only writes it and
+    # the last one writes the rounded result instead).  With one set of G buffers the
     # clients wait for the fold before they reuse a buffer; a second set lets them go on, which gains nothing here
     # (the fold and the encryption kernels share the memory system) and costs the memory a larger G can use.
     acc_none = acc_plain = ct_none = server = server_stream = None
@@ -351,7 +352,8 @@ def run_workload(he, si, torch, name, args, steps, warmup, headline, copy_gbs=No
         if record:
             ev[0].record()
         server_stream.wait_stream(cur)
-        if n_pl:
+        one_group = K <= G                              # then: begin, add, finalize; else the first fold writes the
+        if n_pl and one_group:                          # accumulator and the last one writes the result
             with torch.cuda.stream(server_stream):
                 he.he_aggregate_begin(server, 0, n_pl, acc_none, acc_plain)
         folded = {}                                    # buffer half -> event: the server has read these remainders
@@ -368,15 +370,23 @@ def run_workload(he, si, torch, name, args, steps, warmup, headline, copy_gbs=No
                 sent.record(cur)
                 with torch.cuda.stream(server_stream):
                     server_stream.wait_event(sent)
-                    he.he_aggregate_add(server, alpha[grp[0]:grp[-1] + 1], [None] * len(grp),
-                                        [plains[sl % len(plains)] for sl in slots], acc_none, acc_plain)
+                    fold_args = (server, alpha[grp[0]:grp[-1] + 1], [None] * len(grp), [plains[sl % len(plains)] for sl in slots],
+                                 acc_none, acc_plain)
+                    if one_group:
+                        he.he_aggregate_add(*fold_args)
+                    elif g0 == 0:
+                        he.he_aggregate_add_first(*fold_args)
+                    elif g0 + G >= K:
+                        he.he_aggregate_add_last(*fold_args, ct_none, pl_g)
+                    else:
+                        he.he_aggregate_add(*fold_args)
                     folded[half] = torch.cuda.Event()
                     folded[half].record(server_stream)
         cur.wait_stream(server_stream)
         if record:
             ev[1].record()      # the encrypt phase of this form includes the server's folding of the remainders
         he.he_aggregate(server, alpha, cts, [None] * K, ct_g, None)
-        if n_pl:
+        if n_pl and one_group:
             he.he_aggregate_finalize(server, acc_none, acc_plain, ct_none, pl_g)
         if record:
             ev[2].record()
@@ -506,9 +516,9 @@ def run_workload(he, si, torch, name, args, steps, warmup, headline, copy_gbs=No
     mv_ms, mv_launches = kern.get("plain_move", (0.0, 0))
     pf_ms, pf_launches = kern.get("plain_fedavg", (0.0, 0))
     mv_bytes = 8 * n_pl * (K + 1) * steps                               # K compactions and one scatter: 4 B read + 4 B written each
-    if streamed:   # folds of G clients: K reads, an accumulator read + write per fold, the final read + float32 write
-        folds = -(-K // G)
-        pf_bytes = n_pl * (4 * K + 16 * folds + 8 + 4) * steps
+    if streamed:   # folds of G clients: K reads; the first fold writes the accumulator (8 B), middle ones read and write
+        folds = -(-K // G)                         # it, the last one reads it and writes float32 (one fold: begin, add, finalize)
+        pf_bytes = n_pl * (4 * K + (16 * (folds - 1) + 4 if folds > 1 else 16 + 8 + 4)) * steps
     else:
         pf_bytes = n_pl * (4 * K + 4) * steps
     roofline_plain = None

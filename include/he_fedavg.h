@@ -203,6 +203,22 @@ he_status he_aggregate_add(he_ctx* ctx, uint32_t K_chunk, const double* alpha_ho
 he_status he_aggregate_finalize(he_ctx* ctx, uint64_t n_ct, uint64_t n_plain,
                                 const uint32_t* acc_ct_dev, const double* acc_plain_dev,
                                 uint32_t* ct_out_dev, float* plain_out_dev, void* stream);
+/* The same stream of folds with two passes over the accumulators fewer (they are the extra
+   memory traffic of the streaming form: 8 bytes per plaintext parameter and pass).
+   he_aggregate_add_first is begin + add in one: the accumulators are written, never read, and need
+   no begin.  he_aggregate_add_last is add + finalize in one: the last K_chunk clients are folded
+   in and the rescaled / rounded result goes straight to ct_out_dev / plain_out_dev; the
+   accumulators are read (and, for K_chunk above 64, used for partial sums) and hold nothing
+   defined afterwards.  Results are bit-identical to begin, add ..., finalize. */
+he_status he_aggregate_add_first(he_ctx* ctx, uint32_t K_chunk, const double* alpha_host,
+                                 const uint32_t* const* ct_in_dev, const float* const* plain_in_dev,
+                                 uint64_t n_ct, uint64_t n_plain, uint32_t* acc_ct_dev,
+                                 double* acc_plain_dev, void* stream);
+he_status he_aggregate_add_last(he_ctx* ctx, uint32_t K_chunk, const double* alpha_host,
+                                const uint32_t* const* ct_in_dev, const float* const* plain_in_dev,
+                                uint64_t n_ct, uint64_t n_plain, uint32_t* acc_ct_dev,
+                                double* acc_plain_dev, uint32_t* ct_out_dev, float* plain_out_dev,
+                                void* stream);
 
 /* ---- client: W <- HE.Dec(sk, M . [W_glob]) + (1-M) . [W_glob] -------------------------- */
 

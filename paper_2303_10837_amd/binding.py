@@ -54,6 +54,10 @@ _SIGS = {
     "he_aggregate_begin": (C.c_int32, [_P, C.c_uint64, C.c_uint64, _P, _P, _P]),
     "he_aggregate_add": (C.c_int32, [_P, C.c_uint32, C.POINTER(C.c_double), C.POINTER(_P), C.POINTER(_P),
                                      C.c_uint64, C.c_uint64, _P, _P, _P]),
+    "he_aggregate_add_first": (C.c_int32, [_P, C.c_uint32, C.POINTER(C.c_double), C.POINTER(_P), C.POINTER(_P),
+                                           C.c_uint64, C.c_uint64, _P, _P, _P]),
+    "he_aggregate_add_last": (C.c_int32, [_P, C.c_uint32, C.POINTER(C.c_double), C.POINTER(_P), C.POINTER(_P),
+                                          C.c_uint64, C.c_uint64, _P, _P, _P, _P, _P]),
     "he_aggregate_finalize": (C.c_int32, [_P, C.c_uint64, C.c_uint64, _P, _P, _P, _P, _P]),
     "he_decrypt_merge": (C.c_int32, [_P, _P, _P, _P, _P, _P, _P]),
     "he_encrypt_masked_weighted": (C.c_int32, [_P, _P, _P, C.c_uint64, C.c_uint32, C.c_double, _P, _P, _P, _P]),
@@ -305,6 +309,34 @@ def he_aggregate_add(ctx, alphas, cts, plains, acc_ct, acc_plain):
     pp = _ptr_array(plains, torch.float32) if n_plain else None
     _check(load().he_aggregate_add(ctx.h, K, a, cp, pp, n_ct, n_plain, _ptr(acc_ct) if n_ct else None,
                                    _ptr(acc_plain) if n_plain else None, _stream()))
+
+
+def he_aggregate_add_first(ctx, alphas, cts, plains, acc_ct, acc_plain):
+    """begin + add in one: the accumulators are written without being read."""
+    K = len(alphas)
+    n_ct, n_plain = acc_ct.shape[0], acc_plain.numel()
+    a = (C.c_double * K)(*[float(x) for x in alphas])
+    cp = _ptr_array(cts, torch.int32) if n_ct else None
+    pp = _ptr_array(plains, torch.float32) if n_plain else None
+    _check(load().he_aggregate_add_first(ctx.h, K, a, cp, pp, n_ct, n_plain, _ptr(acc_ct) if n_ct else None,
+                                         _ptr(acc_plain) if n_plain else None, _stream()))
+
+
+def he_aggregate_add_last(ctx, alphas, cts, plains, acc_ct, acc_plain, ct_out=None, plain_out=None):
+    """add + finalize in one: returns (ct_out, plain_out); the accumulators hold nothing defined afterwards."""
+    K = len(alphas)
+    n_ct, n_plain = acc_ct.shape[0], acc_plain.numel()
+    if ct_out is None:
+        ct_out = torch.empty((n_ct, 2, ctx.L - 1, ctx.N), dtype=torch.int32, device=ctx.device)
+    if plain_out is None:
+        plain_out = torch.empty((n_plain,), dtype=torch.float32, device=ctx.device)
+    a = (C.c_double * K)(*[float(x) for x in alphas])
+    cp = _ptr_array(cts, torch.int32) if n_ct else None
+    pp = _ptr_array(plains, torch.float32) if n_plain else None
+    _check(load().he_aggregate_add_last(ctx.h, K, a, cp, pp, n_ct, n_plain, _ptr(acc_ct) if n_ct else None,
+                                        _ptr(acc_plain) if n_plain else None, _ptr(ct_out) if n_ct else None,
+                                        _ptr(plain_out) if n_plain else None, _stream()))
+    return ct_out, plain_out
 
 
 def he_aggregate_finalize(ctx, acc_ct, acc_plain, ct_out=None, plain_out=None):

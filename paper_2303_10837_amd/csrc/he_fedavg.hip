@@ -2242,21 +2242,52 @@ he_status he_aggregate_begin(he_ctx* ctx, uint64_t n_ct, uint64_t n_plain, uint3
   return on_exception();
 }
 
-he_status he_aggregate_add(he_ctx* ctx, uint32_t K_chunk, const double* alpha_host, const uint32_t* const* ct_in_dev,
-                           const float* const* plain_in_dev, uint64_t n_ct, uint64_t n_plain, uint32_t* acc_ct_dev,
-                           double* acc_plain_dev, void* stream) try {
+// One fold of the streaming form.  has_acc: the accumulators hold earlier clients (otherwise they are only written);
+// fin: the outputs are written instead of the accumulators.
+static he_status aggregate_fold(he_ctx* ctx, uint32_t K_chunk, const double* alpha_host, const uint32_t* const* ct_in_dev,
+                                const float* const* plain_in_dev, uint64_t n_ct, uint64_t n_plain, uint32_t* acc_ct_dev,
+                                double* acc_plain_dev, bool has_acc, bool fin, uint32_t* ct_out_dev, float* plain_out_dev,
+                                void* stream) {
   he_status s = check_ctx(ctx);
   if (s != HE_OK) return s;
   if (K_chunk == 0 || K_chunk > HE_MAX_CLIENTS_PER_CALL) return fail(HE_ERR_INVALID_ARG, "K_chunk must be in 1..HE_MAX_CLIENTS_PER_CALL");
-  if (!alpha_host || (n_ct && (!ct_in_dev || !acc_ct_dev)) || (n_plain && (!plain_in_dev || !acc_plain_dev)))
+  // a fold of more clients than one launch takes keeps its partial sums in the accumulators, whatever it ends with
+  const bool needs_acc = has_acc || !fin || K_chunk > (uint32_t)kAggClients;
+  if (!alpha_host || (n_ct && (!ct_in_dev || (needs_acc && !acc_ct_dev))) || (n_plain && (!plain_in_dev || (needs_acc && !acc_plain_dev))))
     return fail(HE_ERR_INVALID_ARG, "null argument");
+  if (fin && ((n_ct && !ct_out_dev) || (n_plain && !plain_out_dev))) return fail(HE_ERR_INVALID_ARG, "null output");
   for (uint32_t i = 0; i < K_chunk; ++i)
     if ((n_ct && !ct_in_dev[i]) || (n_plain && !plain_in_dev[i])) return fail(HE_ERR_INVALID_ARG, "null client buffer");
   std::vector<uint32_t> w;
   s = integer_weights(ctx, K_chunk, alpha_host, false, &w);
   if (s != HE_OK) return s;
-  return aggregate_impl(ctx, K_chunk, alpha_host, w, ct_in_dev, plain_in_dev, n_ct, n_plain, true, false, acc_ct_dev,
-                        acc_plain_dev, nullptr, nullptr, static_cast<hipStream_t>(stream));
+  return aggregate_impl(ctx, K_chunk, alpha_host, w, ct_in_dev, plain_in_dev, n_ct, n_plain, has_acc, fin, acc_ct_dev,
+                        acc_plain_dev, ct_out_dev, plain_out_dev, static_cast<hipStream_t>(stream));
+}
+
+he_status he_aggregate_add(he_ctx* ctx, uint32_t K_chunk, const double* alpha_host, const uint32_t* const* ct_in_dev,
+                           const float* const* plain_in_dev, uint64_t n_ct, uint64_t n_plain, uint32_t* acc_ct_dev,
+                           double* acc_plain_dev, void* stream) try {
+  return aggregate_fold(ctx, K_chunk, alpha_host, ct_in_dev, plain_in_dev, n_ct, n_plain, acc_ct_dev, acc_plain_dev, true, false,
+                        nullptr, nullptr, stream);
+} catch (...) {
+  return on_exception();
+}
+
+he_status he_aggregate_add_first(he_ctx* ctx, uint32_t K_chunk, const double* alpha_host, const uint32_t* const* ct_in_dev,
+                                 const float* const* plain_in_dev, uint64_t n_ct, uint64_t n_plain, uint32_t* acc_ct_dev,
+                                 double* acc_plain_dev, void* stream) try {
+  return aggregate_fold(ctx, K_chunk, alpha_host, ct_in_dev, plain_in_dev, n_ct, n_plain, acc_ct_dev, acc_plain_dev, false, false,
+                        nullptr, nullptr, stream);
+} catch (...) {
+  return on_exception();
+}
+
+he_status he_aggregate_add_last(he_ctx* ctx, uint32_t K_chunk, const double* alpha_host, const uint32_t* const* ct_in_dev,
+                                const float* const* plain_in_dev, uint64_t n_ct, uint64_t n_plain, uint32_t* acc_ct_dev,
+                                double* acc_plain_dev, uint32_t* ct_out_dev, float* plain_out_dev, void* stream) try {
+  return aggregate_fold(ctx, K_chunk, alpha_host, ct_in_dev, plain_in_dev, n_ct, n_plain, acc_ct_dev, acc_plain_dev, true, true,
+                        ct_out_dev, plain_out_dev, stream);
 } catch (...) {
   return on_exception();
 }

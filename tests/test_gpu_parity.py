@@ -188,6 +188,19 @@ def test_aggregate_and_streaming(he, log2_n, limbs, K):
     # the accumulator before the rescale is the plain weighted sum of residues
     acc = _np(acc_ct).astype(np.int64)
     assert np.array_equal(acc[1], osch.weighted_sum(p, [x[1] for x in cts], alpha))
+    # the same folds with the first one writing the accumulators (never zeroed: they start as garbage) and the last one
+    # writing the outputs -> identical bytes again
+    if K >= 2:
+        acc_ct2 = torch.full_like(acc_ct, 0x5A5A5A5A)
+        acc_pl2 = torch.full_like(acc_pl, float("nan"))
+        chunks = [(lo, hi) for lo, hi in [(0, cut), (cut, cut2), (cut2, K)] if hi > lo]
+        lo, hi = chunks[0]
+        he.he_aggregate_add_first(ctx, alpha[lo:hi], d_cts[lo:hi], d_pl[lo:hi], acc_ct2, acc_pl2)
+        for lo, hi in chunks[1:-1]:
+            he.he_aggregate_add(ctx, alpha[lo:hi], d_cts[lo:hi], d_pl[lo:hi], acc_ct2, acc_pl2)
+        lo, hi = chunks[-1]
+        ct_f, pl_f = he.he_aggregate_add_last(ctx, alpha[lo:hi], d_cts[lo:hi], d_pl[lo:hi], acc_ct2, acc_pl2)
+        assert torch.equal(ct_f, ct_s) and torch.equal(pl_f, pl_g)
 
 
 def test_aggregate_special_cases(he):
