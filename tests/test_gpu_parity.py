@@ -219,6 +219,18 @@ def test_aggregate_special_cases(he):
     for bad in ([0.5, 0.6], [1.5, -0.5], [1e-12, 1.0 - 1e-12]):
         with pytest.raises(he.HeError):
             he.he_aggregate(ctx, bad, [d, d], [None, None])
+    # ... by the streaming folds too (their weights need not sum to 1, but each must be a usable weight)
+    acc_ct, acc_pl = he.he_aggregate_begin(ctx, 2, 0)
+    for fold in (he.he_aggregate_add, he.he_aggregate_add_first, he.he_aggregate_add_last):
+        with pytest.raises(he.HeError):
+            fold(ctx, [0.5, -0.25], [d, d], [None, None], acc_ct, acc_pl)
+        with pytest.raises(he.HeError):
+            fold(ctx, [0.5, 1e-12], [d, d], [None, None], acc_ct, acc_pl)
+    # two clients through first + last only (no begin, no middle fold, no finalize)
+    he.he_aggregate_add_first(ctx, [0.25], [d], [None], acc_ct, acc_pl)
+    out2, _ = he.he_aggregate_add_last(ctx, [0.75], [d], [None], acc_ct, acc_pl)
+    ref2, _ = he.he_aggregate(ctx, [0.25, 0.75], [d, d], [None, None])
+    assert torch.equal(out2, ref2)
 
 
 @pytest.mark.parametrize("log2_n,limbs", [(4, 3), (10, 3), (13, 3), (14, 4), (10, 2)])
