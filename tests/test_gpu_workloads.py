@@ -67,10 +67,14 @@ def _run_workload(he, w, device_inputs, stream_plain, clients_checked, cts_extra
 
     cts, slots_host, plain_host = [], {}, []
     ref64 = torch.zeros(P, dtype=torch.float64, device="cuda")            # float64 FedAvg of everything
-    acc_plain = acc_none = None
+    acc_plain = acc_none = pl_g = None
     plains = []
+    G = 4                                                                 # remainders folded per server call when streamed
     if stream_plain and n_plain:
-        acc_none, acc_plain = he.he_aggregate_begin(ctx, 0, n_plain)      # plain part only: no ciphertext accumulator
+        assert K > G                                                      # first fold, middle folds, last fold
+        acc_none = torch.empty((0, 2, L, N), dtype=torch.int32, device="cuda")   # plain part only: no ciphertext accumulator
+        acc_plain = torch.full((n_plain,), float("nan"), dtype=torch.float64, device="cuda")   # never zeroed: the first fold writes it
+        ct_none = torch.empty((0, 2, L - 1, N), dtype=torch.int32, device="cuda")
     plain_ref64 = torch.zeros(n_plain, dtype=torch.float64, device="cuda") if n_plain else None
     for i in range(K):
         wi = si.client_params_torch(w, i, "cuda") if device_inputs else torch.from_numpy(si.client_params_numpy(w, i)).cuda()
@@ -87,23 +91,29 @@ def _run_workload(he, w, device_inputs, stream_plain, clients_checked, cts_extra
             prod = float(alpha[i]) * pl.double()
             plain_ref64 = plain_ref64 + prod
             del prod
-            if stream_plain:
-                he.he_aggregate_add(ctx, alpha[i:i + 1], [None], [pl], acc_none, acc_plain)
-            else:
-                plains.append(pl)
-        del wi
-        if stream_plain:
-            del pl
+            plains.append(pl)
+            if stream_plain and (len(plains) == G or i == K - 1):         # the streamed form of bench.py: groups of remainders
+                lo = i + 1 - len(plains)
+                args = (ctx, alpha[lo:i + 1], [None] * len(plains), plains, acc_none, acc_plain)
+                if lo == 0:
+                    he.he_aggregate_add_first(*args)
+                elif i == K - 1:
+                    _, pl_g = he.he_aggregate_add_last(*args, ct_none, None)
+                else:
+                    he.he_aggregate_add(*args)
+                plains = []
+        del wi, pl
     print(f"[{w.name}] encrypted {K} x {n_ct} ciphertexts", flush=True)
 
     # ---- server ----
     if stream_plain and n_plain:
         ct_g, _ = he.he_aggregate(ctx, alpha, cts, [None] * K)
-        _, pl_g = he.he_aggregate_finalize(ctx, acc_none, acc_plain)
     else:
         ct_g, pl_g = he.he_aggregate(ctx, alpha, cts, plains if n_plain else [None] * K)
     out = he.he_decrypt_merge(ctx, keys, mask, ct_g, pl_g if n_plain else None)
     torch.cuda.synchronize()
+    acc_plain = plains = None
+    torch.cuda.empty_cache()                                              # the remainder buffers' blocks go back to the device
     print(f"[{w.name}] aggregated and decrypted", flush=True)
 
     # ---- sampled ciphertexts, stage by stage ----
@@ -130,6 +140,8 @@ def _run_workload(he, w, device_inputs, stream_plain, clients_checked, cts_extra
         assert torch.equal(pl_g, plain_ref64.float()), "plain FedAvg differs from the float64 evaluation"
         assert np.array_equal(pl_g[torch.from_numpy(plain_probe).cuda()].cpu().numpy(), ofed.plain_fedavg(plain_host, alpha))
         assert torch.equal(out[torch.from_numpy(plain_probe_param).cuda()], pl_g[torch.from_numpy(plain_probe).cuda()])
+    plain_ref64 = None
+    torch.cuda.empty_cache()
     # ---- whole model against float64 FedAvg ----
     is_enc = torch.zeros(P, dtype=torch.bool, device="cuda")
     for s, ln in zip(starts, lens):
