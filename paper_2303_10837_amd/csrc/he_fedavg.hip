@@ -1283,6 +1283,12 @@ void launch_ntt_batch(const RingDev& rg, bool inverse, int limb, uint32_t* polys
   } else if (rg.logN == 13) {
     if (inverse) hipLaunchKernelGGL((k_ntt_batch_s<13, true>), grid, dim3(NttPlan<13>::NT), static_lds_bytes(13, 1), st, rg, limb, polys);
     else hipLaunchKernelGGL((k_ntt_batch_s<13, false>), grid, dim3(NttPlan<13>::NT), static_lds_bytes(13, 1), st, rg, limb, polys);
+  } else if (rg.logN == 12) {
+    if (inverse) hipLaunchKernelGGL((k_ntt_batch_s<12, true>), grid, dim3(NttPlan<12>::NT), static_lds_bytes(12, 1), st, rg, limb, polys);
+    else hipLaunchKernelGGL((k_ntt_batch_s<12, false>), grid, dim3(NttPlan<12>::NT), static_lds_bytes(12, 1), st, rg, limb, polys);
+  } else if (rg.logN == 11) {
+    if (inverse) hipLaunchKernelGGL((k_ntt_batch_s<11, true>), grid, dim3(NttPlan<11>::NT), static_lds_bytes(11, 1), st, rg, limb, polys);
+    else hipLaunchKernelGGL((k_ntt_batch_s<11, false>), grid, dim3(NttPlan<11>::NT), static_lds_bytes(11, 1), st, rg, limb, polys);
   } else {
     if (inverse) hipLaunchKernelGGL(k_ntt_batch<true>, grid, dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 1), st, rg, limb, polys);
     else hipLaunchKernelGGL(k_ntt_batch<false>, grid, dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 1), st, rg, limb, polys);
@@ -1363,6 +1369,12 @@ he_status launch_encrypt(he_ctx* ctx, const he_pk* pk, uint64_t n_ct, const int3
   else if (rg.logN == 13)
     hipLaunchKernelGGL(k_encrypt_s<13>, grid_x, dim3(NttPlan<13>::NT), static_lds_bytes(13, 1), st, rg, pk->tab, rnd.u, m, rnd.e0, rnd.e1,
                        ct_out, (uint32_t)n_ct);
+  else if (rg.logN == 12)
+    hipLaunchKernelGGL(k_encrypt_s<12>, grid_x, dim3(NttPlan<12>::NT), static_lds_bytes(12, 1), st, rg, pk->tab, rnd.u, m, rnd.e0, rnd.e1,
+                       ct_out, (uint32_t)n_ct);
+  else if (rg.logN == 11)
+    hipLaunchKernelGGL(k_encrypt_s<11>, grid_x, dim3(NttPlan<11>::NT), static_lds_bytes(11, 1), st, rg, pk->tab, rnd.u, m, rnd.e0, rnd.e1,
+                       ct_out, (uint32_t)n_ct);
   else
     hipLaunchKernelGGL(k_encrypt, grid, dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 2), st, rg, pk->tab, rnd.u, m, rnd.e0, rnd.e1, ct_out);
   HIP_TRY(hipGetLastError());
@@ -1379,6 +1391,10 @@ he_status launch_decrypt(he_ctx* ctx, const he_sk* sk, const uint32_t* ct, uint6
       hipLaunchKernelGGL(k_decrypt_s<14>, grid, dim3(NttPlan<14>::NT), static_lds_bytes(14, 1), st, rg, sk->tab, ct, level, d_out);
     else if (rg.logN == 13)
       hipLaunchKernelGGL(k_decrypt_s<13>, grid, dim3(NttPlan<13>::NT), static_lds_bytes(13, 1), st, rg, sk->tab, ct, level, d_out);
+    else if (rg.logN == 12)
+      hipLaunchKernelGGL(k_decrypt_s<12>, grid, dim3(NttPlan<12>::NT), static_lds_bytes(12, 1), st, rg, sk->tab, ct, level, d_out);
+    else if (rg.logN == 11)
+      hipLaunchKernelGGL(k_decrypt_s<11>, grid, dim3(NttPlan<11>::NT), static_lds_bytes(11, 1), st, rg, sk->tab, ct, level, d_out);
     else
       hipLaunchKernelGGL(k_decrypt, grid, dim3(ntt_threads(rg.N)), ntt_lds_bytes(rg.N, 1), st, rg, sk->tab, ct, level, d_out);
   }

@@ -1,4 +1,4 @@
-// Compile-time specialised negacyclic NTT passes for the tuned ring sizes (N = 2^13, 2^14).
+// Compile-time specialised negacyclic NTT passes for the tuned ring sizes (N = 2^11 ... 2^14).
 //
 // Same mathematics as the generic passes in he_device.hpp; what changes is that the ring
 // size, the pass plan and the workgroup size are template parameters, so that
@@ -10,9 +10,11 @@
 //     barriers (see owned_group), and
 //   * the Shoup products take three instructions (mul_shoup_mad).
 //
-// Plan: N = 2^14 -> stages 4+4+3+3 (strides 1024, 64, 8, 1); N = 2^13 -> 4+3+3+3 (512, 64, 8, 1).
-// N/16 threads per workgroup: every thread owns 16 coefficients per pass (one group of 16 or
-// two groups of 8).
+// Plan: N = 2^14 -> stages 4+4+3+3 (strides 1024, 64, 8, 1); N = 2^13 -> 4+3+3+3 (512, 64, 8, 1);
+// N = 2^12 -> 2+4+3+3 (1024, 64, 8, 1); N = 2^11 -> 1+4+3+3 (1024, 64, 8, 1).  The last pass always works on groups of
+// 8 (the fused middle of the encrypt / decrypt pipelines), and the blocks that passes 1..3 stay inside hold at least
+// 1024 coefficients, so that every pass has whole wavefronts of groups per block.
+// N/16 threads per workgroup: every thread owns 16 coefficients per pass.
 #pragma once
 #include "he_device.hpp"
 
@@ -38,6 +40,21 @@ struct NttPlan<13> {
   static constexpr int R[4] = {4, 3, 3, 3};
   static constexpr int S[4] = {0, 4, 7, 10};
   static constexpr int NT = 512;
+};
+
+template <>
+struct NttPlan<12> {
+  static constexpr int kPasses = 4;
+  static constexpr int R[4] = {2, 4, 3, 3};
+  static constexpr int S[4] = {0, 2, 6, 9};
+  static constexpr int NT = 256;
+};
+template <>
+struct NttPlan<11> {
+  static constexpr int kPasses = 4;
+  static constexpr int R[4] = {1, 4, 3, 3};
+  static constexpr int S[4] = {0, 1, 5, 8};
+  static constexpr int NT = 128;
 };
 
 template <int LOGN, int S0, int R>
@@ -144,8 +161,9 @@ __device__ __forceinline__ void lds_store_group(uint32_t* x, int g, const uint32
   }
 }
 
-// Passes 1..3 never leave a block of N/16 consecutive coefficients (pass 1 starts at stage 4),
-// and one such block is exactly 64 pass-1 groups: one wavefront.  Wave w of a workgroup of NT
+// Passes 1..3 never leave a block of N >> S[1] consecutive coefficients (pass 1 starts at stage S[1]: N/16 coefficients
+// for N = 2^13 and 2^14, 1024 for the smaller rings), and one such block is a whole number of wavefronts of groups in
+// each of these passes.  Wave w of a workgroup of NT
 // threads therefore OWNS blocks w, w + NT/64, ... through passes 1, 2 and 3 of the forward
 // transform and 3, 2, 1 of the inverse: the data it reads in one of these passes was written by
 // itself in the previous one, so those passes are separated by a wavefront-level ordering point
@@ -154,10 +172,10 @@ __device__ __forceinline__ void lds_store_group(uint32_t* x, int g, const uint32
 template <int LOGN, int PASS, int NT>
 __device__ __forceinline__ int owned_group(int it) {
   using P = NttPlan<LOGN>;
-  static_assert(P::S[1] == 4 && PASS >= 1, "blocks of N/16 coefficients start at pass 1");
-  constexpr int GPB = ((1 << LOGN) / 16) >> P::R[PASS];  // groups per block in this pass
+  static_assert(PASS >= 1, "blocks start at pass 1");
+  constexpr int GPB = ((1 << LOGN) >> P::S[1]) >> P::R[PASS];  // groups per block in this pass
   constexpr int NW = NT / 64;
-  static_assert(NT % 64 == 0 && 16 % NW == 0 && GPB % 64 == 0, "whole wavefronts per block");
+  static_assert(NT % 64 == 0 && (1 << P::S[1]) % NW == 0 && GPB % 64 == 0, "whole wavefronts per block");
   const int local = it * 64 + (int)(threadIdx.x & 63);
   return ((int)(threadIdx.x >> 6) + NW * (local / GPB)) * GPB + (local % GPB);
 }

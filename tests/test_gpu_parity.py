@@ -52,7 +52,7 @@ def _setup(he, log2_n, limbs, eta=21):
     return _CTX_CACHE[key]
 
 
-@pytest.mark.parametrize("log2_n,limbs", [(3, 3), (4, 3), (5, 2), (6, 3), (7, 3), (9, 3), (10, 3), (12, 3), (13, 3), (14, 4)])
+@pytest.mark.parametrize("log2_n,limbs", [(3, 3), (4, 3), (5, 2), (6, 3), (7, 3), (9, 3), (10, 3), (11, 3), (12, 3), (12, 8), (13, 3), (14, 4)])
 def test_context_and_transform(he, log2_n, limbs):
     ctx, _, p, _ = _setup(he, log2_n, limbs)
     assert ctx.primes == p.primes and ctx.N == p.N
@@ -79,7 +79,7 @@ def _boundary_values(rs, q, shape):
     return v
 
 
-@pytest.mark.parametrize("log2_n,limbs", [(10, 3), (13, 3), (14, 4)])
+@pytest.mark.parametrize("log2_n,limbs", [(10, 3), (11, 3), (12, 4), (13, 3), (14, 4)])
 def test_transform_and_decrypt_on_boundary_values(he, log2_n, limbs):
     """Inputs made of the extreme residues (every butterfly sees sums and differences at the edges of [0, q) and
     [0, 2q)): the transforms, and decryption of ciphertexts made of such residues, stay bit-exact."""
@@ -115,7 +115,7 @@ def test_transform_and_decrypt_on_boundary_values(he, log2_n, limbs):
         assert np.array_equal(out[c], osch.aggregate(p, [x[c] for x in ins], alpha)), (log2_n, c)
 
 
-@pytest.mark.parametrize("log2_n,limbs", [(4, 3), (10, 3), (13, 3), (14, 4)])
+@pytest.mark.parametrize("log2_n,limbs", [(4, 3), (10, 3), (11, 2), (12, 3), (13, 3), (14, 4)])
 def test_keygen(he, log2_n, limbs):
     ctx, keys, p, okeys = _setup(he, log2_n, limbs)
     pk, sk = he.he_debug_export_keys(ctx, keys)
@@ -145,7 +145,7 @@ def test_encode(he, log2_n, limbs):
             assert np.abs(m[c] - oenc.encode_def(slots[c].astype(np.float64), log2_n, 30)).max() <= 1
 
 
-@pytest.mark.parametrize("log2_n,limbs,eta", [(4, 3, 21), (10, 3, 21), (13, 3, 21), (14, 4, 21), (13, 3, 0), (10, 2, 32)])
+@pytest.mark.parametrize("log2_n,limbs,eta", [(4, 3, 21), (10, 3, 21), (11, 3, 21), (12, 5, 21), (13, 3, 21), (14, 4, 21), (13, 3, 0), (10, 2, 32), (12, 2, 32)])
 def test_encrypt_given_plaintext(he, log2_n, limbs, eta):
     ctx, keys, p, okeys = _setup(he, log2_n, limbs, eta)
     rs = np.random.default_rng(2)
@@ -233,7 +233,7 @@ def test_aggregate_special_cases(he):
     assert torch.equal(out2, ref2)
 
 
-@pytest.mark.parametrize("log2_n,limbs", [(4, 3), (10, 3), (13, 3), (14, 4), (10, 2)])
+@pytest.mark.parametrize("log2_n,limbs", [(4, 3), (10, 3), (11, 3), (12, 3), (13, 3), (14, 4), (10, 2)])
 def test_decrypt_residues_and_decode(he, log2_n, limbs):
     ctx, keys, p, okeys = _setup(he, log2_n, limbs)
     rs = np.random.default_rng(5)
@@ -306,7 +306,7 @@ MASK_CASES = {
 
 
 @pytest.mark.parametrize("case", list(MASK_CASES))
-@pytest.mark.parametrize("log2_n,limbs", [(10, 3), (13, 3)])
+@pytest.mark.parametrize("log2_n,limbs", [(10, 3), (12, 3), (13, 3)])
 def test_round_small(he, log2_n, limbs, case):
     """Whole path on small vectors, every ciphertext checked: gather, encode (+-1), encrypt
     (bit-exact given the GPU's plaintext), aggregate (bit-exact), decrypt+decode+merge (1e-6)."""
@@ -442,7 +442,7 @@ def test_round_other_chain_lengths(he, log2_n, limbs):
     assert np.abs(out.astype(np.float64) - expect.astype(np.float64)).max() <= 1e-6
 
 
-@pytest.mark.parametrize("log2_n,limbs,seed", [(10, 3, 0), (13, 3, 1), (14, 4, 2)])
+@pytest.mark.parametrize("log2_n,limbs,seed", [(10, 3, 0), (11, 3, 3), (13, 3, 1), (14, 4, 2)])
 def test_round_random_fragmented_masks(he, log2_n, limbs, seed):
     """Masks made of hundreds of short random runs (many of length 1, many ciphertexts that straddle dozens of runs):
     gather, compaction, scatter and merge against the oracle over the whole vector."""
