@@ -86,7 +86,7 @@ typedef struct he_sk he_sk;      /* secret key s, transform domain, device      
 typedef struct he_mask he_mask;  /* selective-encryption mask M as sorted runs, host + device    */
 
 typedef struct {
-  uint32_t log2_n;        /* 3..14; 13 and 14 are the tuned sizes                               */
+  uint32_t log2_n;        /* 3..14; 11 ... 14 run on the specialised kernels                    */
   uint32_t n_limbs;       /* L, 2..HE_MAX_LIMBS                                                 */
   uint32_t scale_bits;    /* log2 of the CKKS scale Delta, 1..30                                */
   uint32_t cbd_eta;       /* centred-binomial parameter of the error, 0..32 (0 = no error)      */

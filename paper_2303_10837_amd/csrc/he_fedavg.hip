@@ -344,7 +344,7 @@ k_decrypt(RingDev rg, const uint2* __restrict__ sk, const uint32_t* __restrict__
       [=](int a, uint32_t v) { out[a] = add_mod(v, c0[a], q); });
 }
 
-// ---- compile-time specialised versions of the three transform kernels (N = 2^13, 2^14) ----
+// ---- compile-time specialised versions of the three transform kernels (N = 2^11 ... 2^14) ----
 // Same results as k_encrypt / k_decrypt / k_ntt_batch; see he_ntt_static.hpp for the plan.
 
 __device__ __forceinline__ void load_key8(const uint2* __restrict__ key, int base, uint2 (&k)[8]) {
@@ -1333,6 +1333,14 @@ he_status launch_encode(he_ctx* ctx, const MaskDev& mk, const float* w, const fl
       hipLaunchKernelGGL(k_encode_r<13>, dim3((uint32_t)n_ct), dim3(FftPlan<11>::NT), static_fft_lds_bytes(11), st, rg, mk, w, slots,
                          first_ct, m_out, key, client, u, e0, e1, pre_scale);
       sampled = true;
+    } else if (rg.logN == 12) {
+      hipLaunchKernelGGL(k_encode_r<12>, dim3((uint32_t)n_ct), dim3(FftPlan<10>::NT), static_fft_lds_bytes(10), st, rg, mk, w, slots,
+                         first_ct, m_out, key, client, u, e0, e1, pre_scale);
+      sampled = true;
+    } else if (rg.logN == 11) {
+      hipLaunchKernelGGL(k_encode_r<11>, dim3((uint32_t)n_ct), dim3(FftPlan<9>::NT), static_fft_lds_bytes(9), st, rg, mk, w, slots,
+                         first_ct, m_out, key, client, u, e0, e1, pre_scale);
+      sampled = true;
     } else {
       hipLaunchKernelGGL(k_encode, dim3((uint32_t)n_ct), dim3(fft_threads(n)), fft_lds_bytes(n), st, rg, mk, w, slots, first_ct, m_out,
                          pre_scale);
@@ -1411,6 +1419,12 @@ void launch_decode_t(he_ctx* ctx, const CrtArgs& ca, const MaskDev& mk, const ui
                        ca, mk, d, first_ct, w_out, slots_out);
   else if (ctx->ring.logN == 13)
     hipLaunchKernelGGL((k_decode_h<13, LEVEL>), dim3((uint32_t)n_ct), dim3(FftPlan<11>::NT), static_fft_lds_bytes(11), st, ctx->ring,
+                       ca, mk, d, first_ct, w_out, slots_out);
+  else if (ctx->ring.logN == 12)
+    hipLaunchKernelGGL((k_decode_h<12, LEVEL>), dim3((uint32_t)n_ct), dim3(FftPlan<10>::NT), static_fft_lds_bytes(10), st, ctx->ring,
+                       ca, mk, d, first_ct, w_out, slots_out);
+  else if (ctx->ring.logN == 11)
+    hipLaunchKernelGGL((k_decode_h<11, LEVEL>), dim3((uint32_t)n_ct), dim3(FftPlan<9>::NT), static_fft_lds_bytes(9), st, ctx->ring,
                        ca, mk, d, first_ct, w_out, slots_out);
   else
     hipLaunchKernelGGL(k_decode<LEVEL>, dim3((uint32_t)n_ct), dim3(fft_threads(n)), fft_lds_bytes(n), st, ctx->ring, ca, mk, d,

@@ -15,6 +15,8 @@
 //   n = 8192 (passes over bits 12-10, 9-7, 6-5, 4-3, 2-0): b5 -> x0^x3, b6 -> x1^x4, b7 -> x2
 //   n = 4096 (passes over bits 11-9, 8-6, 5-3, 2-0):       b5 -> x0, b6 -> x1^x3, b7 -> x2^x4
 //   n = 2048 (passes over bits 10-8, 7-5, 4-2, 1-0):       b5 -> x0^x2, b6 -> x1^x3, b7 -> x4
+// The shorter transforms (n = 1024, 512: the half-length transforms of N = 2^12, 2^11) reuse the last map: any of them
+// is a permutation of the low five bits for fixed higher bits, so the layout is valid at every length of at least 256.
 #pragma once
 #include "he_ntt_static.hpp"
 
@@ -42,6 +44,20 @@ struct FftPlan<11> {  // n = 2048: strides 256, 32, 4, 1
   static constexpr int R[5] = {3, 3, 3, 2, 0};
   static constexpr int S[5] = {0, 3, 6, 9, 11};
   static constexpr int NT = 256;
+};
+template <>
+struct FftPlan<10> {  // n = 1024: strides 128, 16, 4, 1
+  static constexpr int kPasses = 4;
+  static constexpr int R[5] = {3, 3, 2, 2, 0};
+  static constexpr int S[5] = {0, 3, 6, 8, 10};
+  static constexpr int NT = 128;
+};
+template <>
+struct FftPlan<9> {  // n = 512: strides 64, 16, 4, 1
+  static constexpr int kPasses = 4;
+  static constexpr int R[5] = {3, 2, 2, 2, 0};
+  static constexpr int S[5] = {0, 3, 5, 7, 9};
+  static constexpr int NT = 64;
 };
 template <>
 struct FftPlan<12> {  // n = 4096: strides 512, 64, 8, 1

@@ -124,7 +124,7 @@ def test_keygen(he, log2_n, limbs):
     assert np.array_equal(pk[0], okeys.pk_b) and np.array_equal(pk[1], okeys.pk_a)
 
 
-@pytest.mark.parametrize("log2_n,limbs", [(4, 3), (8, 3), (13, 3), (14, 4)])
+@pytest.mark.parametrize("log2_n,limbs", [(4, 3), (8, 3), (11, 3), (12, 3), (13, 3), (14, 4)])
 def test_encode(he, log2_n, limbs):
     ctx, _, p, _ = _setup(he, log2_n, limbs)
     rs = np.random.default_rng(1)
