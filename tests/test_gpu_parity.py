@@ -158,8 +158,25 @@ def test_encrypt_given_plaintext(he, log2_n, limbs, eta):
         assert np.array_equal(ct[c], ref), (c,)
 
 
+@pytest.mark.parametrize("log2_n,limbs", [(13, 3), (12, 2), (14, 5)])
+def test_encrypt_ciphertext_counts_around_the_launch_grouping(he, log2_n, limbs):
+    """The encryption kernel's grid comes in groups of 8 ciphertexts (one per XCD) x L limbs, with the surplus workgroups
+    leaving at once: every count around those groups gives the same ciphertexts as the oracle."""
+    ctx, keys, p, okeys = _setup(he, log2_n, limbs)
+    rs = np.random.default_rng(11)
+    m_all = rs.integers(-(1 << 29), 1 << 29, (17, p.N)).astype(np.int32)
+    ref = {}
+    for n_ct in (1, 7, 8, 9, 16, 17):
+        ct = _np(he.he_debug_encrypt_plain(ctx, keys, SEED + 2, 3, 0, _dev(m_all[:n_ct]))).astype(np.int64)
+        assert ct.shape[0] == n_ct
+        for c in sorted({0, n_ct - 1, n_ct // 2}):
+            if c not in ref:
+                ref[c] = osch.encrypt(p, okeys, m_all[c].astype(np.int64), SEED + 2, 3, c)
+            assert np.array_equal(ct[c], ref[c]), (n_ct, c)
+
+
 @pytest.mark.parametrize("log2_n,limbs,K", [(4, 3, 3), (10, 2, 5), (13, 3, 3), (14, 4, 8), (10, 3, 1), (10, 3, 37), (10, 4, 70), (10, 3, 200),
-                                            (10, 5, 70), (10, 8, 70), (13, 5, 9), (14, 8, 3), (10, 6, 130)])
+                                            (10, 5, 70), (10, 8, 70), (13, 5, 9), (14, 8, 3), (10, 6, 130), (10, 3, 64), (10, 3, 65), (11, 5, 129)])
 def test_aggregate_and_streaming(he, log2_n, limbs, K):
     ctx, _, p, _ = _setup(he, log2_n, limbs)
     rs = np.random.default_rng(3)

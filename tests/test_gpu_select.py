@@ -73,6 +73,28 @@ def test_mask_from_bytes_run_extraction(he, ctx):
     assert _runs(he, mask) == osel.runs_of(m != 0) == [(0, 8), (2040, 16), (4095, 2), (6143, 1)]
 
 
+def test_select_extreme_counts(he, ctx):
+    """k = 1 and k = P - 1 (one entry selected, one entry left out), with the extreme value at either end, in the
+    middle and tied with another entry."""
+    rs = np.random.default_rng(12)
+    P = 2 * 2048 + 333
+    base = rs.random(P).astype(np.float32)
+    for where in (0, P - 1, P // 2):
+        for sign, ratio in ((+1.0, 1.0 / P), (-1.0, (P - 1.0) / P)):
+            sens = base.copy()
+            sens[where] = sign * 5.0                          # the single largest / smallest entry
+            mask = he.he_mask_select_top(ctx, torch.from_numpy(sens).cuda(), ratio)
+            want = osel.select_top(sens, ratio)
+            assert int(want.sum()) == (1 if sign > 0 else P - 1) and want[where] == (sign > 0)
+            assert _runs(he, mask) == osel.runs_of(want)
+            mask.close()
+    sens = base.copy()
+    sens[[5, 4000]] = 7.0                                     # two entries tied for the top: the lower index wins
+    mask = he.he_mask_select_top(ctx, torch.from_numpy(sens).cuda(), 1.0 / P)
+    assert _runs(he, mask) == [(5, 1)]
+    mask.close()
+
+
 def test_unaligned_vectors(he, ctx):
     """Vectors that start at an odd element of an allocation (4-byte and 1-byte aligned only): the kernels' wide
     loads and stores do not apply, the results are the same."""
