@@ -273,6 +273,19 @@ def test_decrypt_residues_and_decode(he, log2_n, limbs):
             assert np.abs(z[c] - ref).max() <= 1e-6 * scale if d is d_rand else np.abs(z[c] - ref).max() <= 1e-9
 
 
+def test_decrypt_residues_beyond_one_launch(he):
+    """More ciphertexts than one launch's grid takes (65535 in its second dimension): the call goes chunk by chunk."""
+    ctx, keys, p, okeys = _setup(he, 11, 2)
+    n_ct = 65536 + 5
+    g = torch.Generator(device="cuda").manual_seed(3)
+    ct = torch.stack([torch.randint(0, q, (n_ct, 2, p.N), generator=g, device="cuda", dtype=torch.int32) for q in p.primes], dim=2).contiguous()
+    d = he.he_debug_decrypt_residues(ctx, keys, ct, 2)
+    assert d.shape == (n_ct, 2, p.N)
+    for c in (0, 32767, 32768, 65534, 65535, 65536, n_ct - 1):
+        ref = osch.decrypt_residues(p, okeys, ct[c].cpu().numpy().astype(np.int64), 2)
+        assert np.array_equal(d[c].cpu().numpy().astype(np.int64), ref), c
+
+
 @pytest.mark.parametrize("log2_n,limbs", [(10, 3), (13, 3), (14, 4), (12, 5)])
 def test_decrypt_merge_at_every_level(he, log2_n, limbs):
     """he_decrypt_merge_level at levels 1 .. L (a fresh ciphertext cut down to its first `level` limbs still decrypts to
