@@ -103,12 +103,28 @@ __device__ __forceinline__ uint32_t run_find(const uint64_t* __restrict__ prefix
   return lo;
 }
 
-// Lookup when the run is known to lie in [lo, hi] (a workgroup's positions span few runs: the
-// bounds are found once per workgroup with uniform loads, the walk here is 0-2 steps).
+// Index of the run that holds packed position t when it is known to lie in [lo, hi] (the bounds are found once per
+// workgroup with uniform loads).  Block-structured masks leave 0-2 steps to walk; under a fragmented mask (a top-p
+// selection over per-parameter sensitivities has runs of one or two entries) a workgroup's positions span hundreds or
+// thousands of runs, and the search inside the bounds is a bisection.
+__device__ __forceinline__ uint32_t run_find_in(const uint64_t* __restrict__ prefix, uint32_t lo, uint32_t hi, uint64_t t) {
+  if (hi - lo <= 4) {
+    uint32_t r = lo;
+    while (r < hi && prefix[r + 1] <= t) ++r;
+    return r;
+  }
+  uint32_t a = lo, b = hi + 1;  // invariant: prefix[a] <= t < prefix[b] (prefix[hi + 1] > t by the caller's bound)
+  while (b - a > 1) {
+    const uint32_t mid = (a + b) >> 1;
+    if (prefix[mid] <= t) a = mid;
+    else b = mid;
+  }
+  return a;
+}
+
 __device__ __forceinline__ uint64_t run_lookup_in(const uint64_t* __restrict__ start, const uint64_t* __restrict__ prefix,
                                                   uint32_t lo, uint32_t hi, uint64_t t) {
-  uint32_t r = lo;
-  while (r < hi && prefix[r + 1] <= t) ++r;
+  const uint32_t r = run_find_in(prefix, lo, hi, t);
   return start[r] + (t - prefix[r]);
 }
 
@@ -781,8 +797,7 @@ k_plain_move(MaskDev mk, const float* __restrict__ src, float* __restrict__ dst)
   if (VEC) {
 #pragma unroll 4
     for (uint64_t t = t0 + 4 * (uint64_t)threadIdx.x; t < t1; t += 4 * 256) {
-      uint32_t r = lo;
-      while (r < hi && mk.cprefix[r + 1] <= t) ++r;
+      const uint32_t r = run_find_in(mk.cprefix, lo, hi, t);
       const uint64_t idx = mk.cstart[r] + (t - mk.cprefix[r]);
       if (t + 4 <= t1 && t + 4 <= mk.cprefix[r + 1]) {  // 4 positions, one run
         if (SCATTER) *reinterpret_cast<v4f_a4*>(dst + idx) = __builtin_nontemporal_load(reinterpret_cast<const v4f_a16*>(src + t));
