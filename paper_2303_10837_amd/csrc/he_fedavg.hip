@@ -47,7 +47,12 @@ struct MaskDev {
   const uint64_t* cprefix;  // [n_cruns + 1]
   uint32_t n_runs, n_cruns;
   uint64_t P, P_enc;
+  // Only for masks whose complement is fragmented (see build_mask_bits); nullptr otherwise.
+  const uint32_t* bits;     // bit i of the array = parameter i is masked; padded with ones to whole chunks of kBitChunk
+  const uint64_t* cchunk;   // [P / kBitChunk + 2] unmasked parameters before parameter c * kBitChunk
 };
+
+constexpr uint32_t kBitChunk = 4096;  // parameters per workgroup of the bit-mask compaction (256 threads x 16)
 
 struct CrtArgs {
   uint32_t qw[kMaxLimbs];  // little-endian words of Q' = prod_{j<level} q_j
@@ -820,8 +825,116 @@ k_plain_move(MaskDev mk, const float* __restrict__ src, float* __restrict__ dst)
   }
 }
 
+// ---- the same two moves under a FRAGMENTED mask ------------------------------------------------
+// When the complement of the mask comes in runs of a few parameters (a top-p selection over per-parameter
+// sensitivities), a position-ordered walk pays a run lookup per 16 bytes.  These kernels go through the model in
+// PARAMETER order instead: a workgroup takes kBitChunk consecutive parameters, a thread 16 of them with their 16 mask
+// bits; the compacted position of an unmasked parameter is the chunk's offset (cchunk) + an exclusive scan of the
+// threads' counts + its rank among the thread's bits.  The model side is a plain unit-stride stream whatever the
+// mask looks like (masked parameters are read and dropped).
+
+// bits from the run list: one thread per 32-bit word; parameters at and beyond P count as masked.
+__global__ void __launch_bounds__(256)
+k_mask_bits(const uint64_t* __restrict__ start, const uint64_t* __restrict__ prefix, uint32_t n_runs, uint64_t P,
+            uint64_t n_words, uint32_t* __restrict__ bits) {
+  const uint64_t wd = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+  if (wd >= n_words) return;
+  const uint64_t i0 = wd * 32;
+  uint32_t out = 0;
+  if (i0 >= P) {
+    out = 0xFFFFFFFFu;
+  } else {
+    // first run that ends after i0 (runs are sorted by start; run r covers [start[r], start[r] + prefix[r+1] - prefix[r]))
+    uint32_t a = 0, b = n_runs;  // answer in [a, b]; b == n_runs means none
+    while (a < b) {
+      const uint32_t mid = (a + b) >> 1;
+      const uint64_t end = start[mid] + (prefix[mid + 1] - prefix[mid]);
+      if (end > i0) b = mid;
+      else a = mid + 1;
+    }
+    for (uint32_t r = a; r < n_runs; ++r) {
+      const uint64_t s0 = start[r];
+      if (s0 >= i0 + 32) break;
+      const uint64_t e0 = s0 + (prefix[r + 1] - prefix[r]);
+      const uint32_t lo = s0 > i0 ? (uint32_t)(s0 - i0) : 0u, hi = e0 < i0 + 32 ? (uint32_t)(e0 - i0) : 32u;  // bits [lo, hi)
+      const uint32_t m_hi = hi >= 32 ? 0xFFFFFFFFu : ((1u << hi) - 1u);
+      out |= m_hi & ~((1u << lo) - 1u);
+    }
+    if (P - i0 < 32) out |= ~((1u << (uint32_t)(P - i0)) - 1u);
+  }
+  bits[wd] = out;
+}
+
+// unmasked parameters per chunk of kBitChunk (128 words): one wavefront per chunk
+__global__ void __launch_bounds__(64)
+k_chunk_unmasked(const uint32_t* __restrict__ bits, uint32_t* __restrict__ counts) {
+  const uint32_t* w = bits + (uint64_t)blockIdx.x * (kBitChunk / 32);
+  uint32_t c = __popc(~w[threadIdx.x]) + __popc(~w[threadIdx.x + 64]);
+  for (int d = 32; d > 0; d >>= 1) c += __shfl_down(c, d, 64);
+  if (threadIdx.x == 0) counts[blockIdx.x] = c;
+}
+
+template <bool SCATTER>
+__global__ void __launch_bounds__(256)
+k_plain_move_bits(MaskDev mk, const float* __restrict__ src, float* __restrict__ dst) {
+  // The chunk's unmasked values pass through LDS in compacted order, so that the compacted side is read / written with
+  // consecutive lanes on consecutive words; the model side moves 16 bytes per lane (scalar where a quad has a masked one).
+  __shared__ float stage[kBitChunk];
+  const uint64_t chunk = blockIdx.x;
+  const uint32_t word = mk.bits[chunk * (kBitChunk / 32) + (threadIdx.x >> 1)];
+  const uint32_t um = ~(word >> (16 * (threadIdx.x & 1))) & 0xFFFFu;  // this thread's 16 parameters: bit set = unmasked
+  uint32_t total;
+  uint32_t r = he_sel::block_exclusive_scan((uint32_t)__popc(um), &total);  // rank of the thread's first unmasked one
+  if (total == 0) return;  // uniform: every thread sees the same total
+  const uint64_t cbase = mk.cchunk[chunk];                              // compacted position of the chunk's first one
+  const uint64_t i0 = chunk * kBitChunk + (uint64_t)threadIdx.x * 16;  // the thread's first parameter
+  if (!SCATTER) {
+    const float* model = src + i0;
+    float x[16];
+    if (i0 + 16 <= mk.P && (reinterpret_cast<uintptr_t>(src) & 15u) == 0) {
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const v4f_a16 q4 = __builtin_nontemporal_load(reinterpret_cast<const v4f_a16*>(model) + v);
+        x[4 * v] = q4.x; x[4 * v + 1] = q4.y; x[4 * v + 2] = q4.z; x[4 * v + 3] = q4.w;
+      }
+    } else {
+#pragma unroll
+      for (int b = 0; b < 16; ++b) x[b] = ((um >> b) & 1u) ? model[b] : 0.f;  // unmasked bits are below P
+    }
+#pragma unroll
+    for (int b = 0; b < 16; ++b)
+      if ((um >> b) & 1u) stage[r++] = x[b];
+    __syncthreads();
+    for (uint32_t j = threadIdx.x; j < total; j += 256) __builtin_nontemporal_store(stage[j], dst + cbase + j);
+  } else {
+    for (uint32_t j = threadIdx.x; j < total; j += 256) stage[j] = __builtin_nontemporal_load(src + cbase + j);
+    __syncthreads();
+    float* model = dst + i0;
+    const bool wide = (reinterpret_cast<uintptr_t>(dst) & 15u) == 0;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const uint32_t quad = (um >> (4 * v)) & 0xFu;
+      if (quad == 0xFu && wide) {
+        v4f_a16 q4;
+        q4.x = stage[r]; q4.y = stage[r + 1]; q4.z = stage[r + 2]; q4.w = stage[r + 3];
+        *(reinterpret_cast<v4f_a16*>(model) + v) = q4;
+        r += 4;
+      } else {
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+          if ((quad >> b) & 1u) model[4 * v + b] = stage[r++];
+      }
+    }
+  }
+}
+
 template <bool SCATTER>
 void launch_plain_move(const MaskDev& mk, const float* src, float* dst, hipStream_t st) {
+  if (mk.bits) {
+    const uint64_t n_pchunks = (mk.P + kBitChunk - 1) / kBitChunk;
+    hipLaunchKernelGGL((k_plain_move_bits<SCATTER>), dim3((uint32_t)n_pchunks), dim3(256), 0, st, mk, src, dst);
+    return;
+  }
   const uint64_t n_plain = mk.P - mk.P_enc;
   const dim3 grid((uint32_t)((n_plain + kMoveChunk - 1) / kMoveChunk)), block(256);
   const bool aligned = reinterpret_cast<uintptr_t>(SCATTER ? (const void*)src : (const void*)dst) % 16 == 0;
@@ -1196,6 +1309,7 @@ struct he_mask {
   he_ctx* ctx;
   MaskDev dev{};
   void* dev_block = nullptr;
+  void* bits_block = nullptr;  // bit mask and per-chunk offsets of a fragmented mask (build_mask_bits)
   uint64_t n_runs = 0;
   // host copy of the run list; masks built on the device (he_mask_from_bytes, he_mask_select_top) fetch it on first use
   mutable std::vector<uint64_t> starts, lens;
@@ -1579,6 +1693,41 @@ he_status aggregate_impl(he_ctx* ctx, uint32_t K, const double* alpha, const std
   return HE_OK;
 }
 
+// A mask whose complement comes in short runs gets a bit mask and per-chunk offsets beside its run tables, and its
+// remainder is then compacted / scattered in parameter order (k_plain_move_bits).  Set-up path: synchronises `st`.
+// Failing to allocate the tables is not an error: the run tables serve every mask.
+// Measured on 400 M parameters (compaction, GB/s of the bytes it has to move): complement runs of 32 / 512 / 2048 / 8192 /
+// 65536 parameters give 2.2 / 3.4 / 4.2 / 4.9 / 5.3 TB/s walking the run list and 3.5 / 4.5 / 4.6 / 4.6 / 4.5 TB/s in parameter order.
+constexpr uint64_t kFragmentedBelow = 4096;  // average complement run (parameters) under which the bit mask is built
+he_status build_mask_bits(he_mask* mk, hipStream_t st) {
+  MaskDev& d = mk->dev;
+  const uint64_t n_plain = d.P - d.P_enc;
+  if (n_plain == 0 || d.n_cruns == 0 || n_plain / d.n_cruns >= kFragmentedBelow) return HE_OK;  // long runs: the run-ordered walk is faster
+  const uint64_t n_pchunks = (d.P + kBitChunk - 1) / kBitChunk;
+  if (n_pchunks >= (1ull << 31)) return HE_OK;
+  const uint64_t n_words = n_pchunks * (kBitChunk / 32);
+  const size_t bits_bytes = n_words * sizeof(uint32_t);
+  const size_t cnt_bytes = ((n_pchunks * sizeof(uint32_t) + 255) / 256) * 256;
+  const size_t off_bytes = (n_pchunks + 2) * sizeof(uint64_t);
+  if (hipMalloc(&mk->bits_block, bits_bytes + cnt_bytes + off_bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    mk->bits_block = nullptr;
+    return HE_OK;
+  }
+  char* base = static_cast<char*>(mk->bits_block);
+  uint32_t* bits = reinterpret_cast<uint32_t*>(base);
+  uint32_t* counts = reinterpret_cast<uint32_t*>(base + bits_bytes);
+  uint64_t* cchunk = reinterpret_cast<uint64_t*>(base + bits_bytes + cnt_bytes);
+  hipLaunchKernelGGL(k_mask_bits, dim3((uint32_t)((n_words + 255) / 256)), dim3(256), 0, st, d.start, d.prefix, d.n_runs, d.P, n_words, bits);
+  hipLaunchKernelGGL(k_chunk_unmasked, dim3((uint32_t)n_pchunks), dim3(64), 0, st, bits, counts);
+  hipLaunchKernelGGL(he_sel::k_scan_counts, dim3(1), dim3(1024), 0, st, counts, n_pchunks, cchunk, (uint64_t)0, (uint64_t)0);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipStreamSynchronize(st));
+  d.bits = bits;
+  d.cchunk = cchunk;
+  return HE_OK;
+}
+
 }  // namespace
 
 // =========================================================================================
@@ -1893,6 +2042,11 @@ he_status he_mask_create(he_ctx* ctx, uint64_t P, const uint64_t* starts, const 
   mk->dev.n_cruns = (uint32_t)cs_v.size();
   mk->dev.P = P;
   mk->dev.P_enc = packed;
+  const he_status sb = build_mask_bits(mk, nullptr);
+  if (sb != HE_OK) {
+    he_mask_destroy(mk);
+    return sb;
+  }
   *out = mk;
   return HE_OK;
 } catch (...) {
@@ -1990,6 +2144,11 @@ static he_status mask_from_device_bytes(he_ctx* ctx, uint64_t P, const uint8_t* 
   mk->dev.n_cruns = (uint32_t)n_cruns;
   mk->dev.P = P;
   mk->dev.P_enc = P_enc;
+  const he_status sb = build_mask_bits(mk, st);
+  if (sb != HE_OK) {
+    he_mask_destroy(mk);
+    return sb;
+  }
   *out = mk;
   return HE_OK;
 } catch (...) {
@@ -2072,6 +2231,7 @@ he_status he_mask_select_top(he_ctx* ctx, uint64_t P, const float* s_dev, double
 void he_mask_destroy(he_mask* mask) {
   if (!mask) return;
   if (mask->dev_block) (void)hipFree(mask->dev_block);
+  if (mask->bits_block) (void)hipFree(mask->bits_block);
   delete mask;
 }
 

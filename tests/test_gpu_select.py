@@ -5,7 +5,9 @@ import numpy as np
 import pytest
 import torch
 
+from oracle import encoder as oenc
 from oracle import fedavg as ofed
+from oracle import scheme as osch
 from oracle import select as osel
 from oracle.params import Params
 
@@ -176,3 +178,52 @@ def test_mask_agreement_flow(he):
     w = rs.normal(0, 0.05, P).astype(np.float32)
     ct, plain = he.he_encrypt_masked(ctx, keys, mask, seed, 0, torch.from_numpy(w).cuda())
     assert ct.shape[0] == mask.n_ct and np.array_equal(plain.cpu().numpy(), w[~want])
+
+
+def test_round_under_a_per_parameter_selection(he):
+    """A whole round under the mask a top-p selection over per-parameter sensitivities gives: runs of one or two
+    parameters (about 180 k of them here), so that a ciphertext's slots and a chunk of the remainder span thousands of
+    runs.  Compaction and merge are checked over the whole vector, sampled ciphertexts through every stage."""
+    log2_n, L, K, seed = 13, 3, 3, 41
+    ctx = he.Context(log2_n, L)
+    keys = he.he_keygen(ctx, seed)
+    p = Params(log2_n, L)
+    okeys = osch.keygen(p, seed)
+    n, P, ratio = p.n_slots, 2_000_003, 0.1
+    rs = np.random.default_rng(13)
+    sens = rs.random(P).astype(np.float32)
+    mask = he.he_mask_select_top(ctx, torch.from_numpy(sens).cuda(), ratio)
+    want = osel.select_top(sens, ratio)
+    starts, lens = he.he_mask_runs(mask)
+    assert len(starts) > 150_000 and list(zip(starts, lens)) == osel.runs_of(want)
+    enc_idx, plain_idx = np.nonzero(want)[0], np.nonzero(~want)[0]
+    assert mask.P_enc == len(enc_idx) and mask.n_ct == -(-len(enc_idx) // n)
+    ws = [rs.normal(0, 0.02, P).astype(np.float32) for _ in range(K)]
+    alpha = np.array([0.2, 0.5, 0.3])
+    cts, pls = [], []
+    for i in range(K):
+        ct, pl = he.he_encrypt_masked(ctx, keys, mask, seed + 1, i, torch.from_numpy(ws[i]).cuda())
+        assert np.array_equal(pl.cpu().numpy(), ws[i][plain_idx])                 # compaction, whole vector
+        cts.append(ct); pls.append(pl)
+    ct_g, pl_g = he.he_aggregate(ctx, alpha, cts, pls)
+    out = he.he_decrypt_merge(ctx, keys, mask, ct_g, pl_g).cpu().numpy()
+    assert np.array_equal(pl_g.cpu().numpy(), ofed.plain_fedavg([w[plain_idx] for w in ws], alpha))
+    assert np.array_equal(out[plain_idx], pl_g.cpu().numpy())                      # scatter, whole vector
+    for c in (0, mask.n_ct // 2, mask.n_ct - 1):                                   # the last one is ragged
+        idx = enc_idx[c * n:(c + 1) * n]
+        ct_c = []
+        for i in range(K):
+            z = np.zeros(n, dtype=np.float32)
+            z[:len(idx)] = ws[i][idx]
+            m = oenc.encode_fft(z.astype(np.float64), log2_n, 30)
+            m_gpu = he.he_debug_encode(ctx, torch.from_numpy(z[None]).cuda())[0].cpu().numpy().astype(np.int64)
+            assert np.abs(m_gpu - m).max() <= 1
+            ref = osch.encrypt(p, okeys, m_gpu, seed + 1, i, c)
+            assert np.array_equal(cts[i][c].cpu().numpy().astype(np.int64), ref), (i, c)   # the gather fed the right slots
+            ct_c.append(ref)
+        agg = osch.aggregate(p, ct_c, alpha)
+        assert np.array_equal(ct_g[c].cpu().numpy().astype(np.int64), agg)
+        zdec = ofed.decode_ct(p, okeys, agg)
+        assert np.abs(out[idx].astype(np.float64) - zdec[:len(idx)].astype(np.float32).astype(np.float64)).max() <= 1e-6
+    ref = ofed.fedavg_float64(ws, alpha)
+    assert np.abs(out[enc_idx] - ref[enc_idx]).max() < 16 * ofed.noise_sigma(p, alpha)
