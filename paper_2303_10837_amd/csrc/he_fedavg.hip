@@ -50,6 +50,7 @@ struct MaskDev {
   // Only for masks whose complement is fragmented (see build_mask_bits); nullptr otherwise.
   const uint32_t* bits;     // bit i of the array = parameter i is masked; padded with ones to whole chunks of kBitChunk
   const uint64_t* cchunk;   // [P / kBitChunk + 2] unmasked parameters before parameter c * kBitChunk
+  const uint32_t* ptab;     // [P_enc / 64 + 2] index of the masked run that holds packed position 64 k (the last entries: n_runs - 1)
 };
 
 constexpr uint32_t kBitChunk = 4096;  // parameters per workgroup of the bit-mask compaction (256 threads x 16)
@@ -131,6 +132,16 @@ __device__ __forceinline__ uint64_t run_lookup_in(const uint64_t* __restrict__ s
                                                   uint32_t lo, uint32_t hi, uint64_t t) {
   const uint32_t r = run_find_in(prefix, lo, hi, t);
   return start[r] + (t - prefix[r]);
+}
+
+// Lookup of packed position t of a ciphertext whose positions span the runs [lo, hi]: with the table of a fragmented mask
+// (the run of every 64th position) the bounds shrink to the at most 65 runs around t before the bisection.
+__device__ __forceinline__ uint64_t run_lookup_ct(const MaskDev& mk, uint32_t lo, uint32_t hi, uint64_t t) {
+  if (mk.ptab && hi - lo > 8) {
+    lo = mk.ptab[t >> 6];
+    hi = mk.ptab[(t >> 6) + 1];
+  }
+  return run_lookup_in(mk.start, mk.prefix, lo, hi, t);
 }
 
 // ---- a1 + a2: gather under the mask and encode one ciphertext's slots -------------------
@@ -250,7 +261,7 @@ k_encode_r(RingDev rg, MaskDev mk, const float* __restrict__ w, const float* __r
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const uint64_t t = t_first + threadIdx.x + u * P::NT;
-        z[u] = t < mk.P_enc ? w[run_lookup_in(mk.start, mk.prefix, r_lo, r_hi, t)] : 0.f;
+        z[u] = t < mk.P_enc ? w[run_lookup_ct(mk, r_lo, r_hi, t)] : 0.f;
       }
     }
   }
@@ -775,7 +786,7 @@ k_decode_h(RingDev rg, CrtArgs ca, MaskDev mk, const uint32_t* __restrict__ d, u
       slots_out[c_local * n + j] = z;
     } else {
       const uint64_t t = c * (uint64_t)n + (uint64_t)j;
-      if (t < mk.P_enc) w_out[run_lookup_in(mk.start, mk.prefix, r_lo, r_hi, t)] = (float)z;
+      if (t < mk.P_enc) w_out[run_lookup_ct(mk, r_lo, r_hi, t)] = (float)z;
     }
   }
 }
@@ -863,6 +874,14 @@ k_mask_bits(const uint64_t* __restrict__ start, const uint64_t* __restrict__ pre
     if (P - i0 < 32) out |= ~((1u << (uint32_t)(P - i0)) - 1u);
   }
   bits[wd] = out;
+}
+
+// ptab[k] = masked run that holds packed position 64 k; entries at and beyond P_enc: the last run
+__global__ void __launch_bounds__(256)
+k_mask_ptab(const uint64_t* __restrict__ prefix, uint32_t n_runs, uint64_t P_enc, uint64_t n_entries, uint32_t* __restrict__ ptab) {
+  const uint64_t k = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+  if (k >= n_entries) return;
+  ptab[k] = 64 * k < P_enc ? run_find(prefix, n_runs, 64 * k) : n_runs - 1;
 }
 
 // unmasked parameters per chunk of kBitChunk (128 words): one wavefront per chunk
@@ -1708,8 +1727,9 @@ he_status build_mask_bits(he_mask* mk, hipStream_t st) {
   const uint64_t n_words = n_pchunks * (kBitChunk / 32);
   const size_t bits_bytes = n_words * sizeof(uint32_t);
   const size_t cnt_bytes = ((n_pchunks * sizeof(uint32_t) + 255) / 256) * 256;
-  const size_t off_bytes = (n_pchunks + 2) * sizeof(uint64_t);
-  if (hipMalloc(&mk->bits_block, bits_bytes + cnt_bytes + off_bytes) != hipSuccess) {
+  const size_t off_bytes = (((n_pchunks + 2) * sizeof(uint64_t) + 255) / 256) * 256;
+  const uint64_t n_ptab = d.n_runs ? d.P_enc / 64 + 2 : 0;  // the run of every 64th packed position, for gather and scatter
+  if (hipMalloc(&mk->bits_block, bits_bytes + cnt_bytes + off_bytes + n_ptab * sizeof(uint32_t)) != hipSuccess) {
     (void)hipGetLastError();
     mk->bits_block = nullptr;
     return HE_OK;
@@ -1721,10 +1741,14 @@ he_status build_mask_bits(he_mask* mk, hipStream_t st) {
   hipLaunchKernelGGL(k_mask_bits, dim3((uint32_t)((n_words + 255) / 256)), dim3(256), 0, st, d.start, d.prefix, d.n_runs, d.P, n_words, bits);
   hipLaunchKernelGGL(k_chunk_unmasked, dim3((uint32_t)n_pchunks), dim3(64), 0, st, bits, counts);
   hipLaunchKernelGGL(he_sel::k_scan_counts, dim3(1), dim3(1024), 0, st, counts, n_pchunks, cchunk, (uint64_t)0, (uint64_t)0);
+  uint32_t* ptab = reinterpret_cast<uint32_t*>(base + bits_bytes + cnt_bytes + off_bytes);
+  if (n_ptab)
+    hipLaunchKernelGGL(k_mask_ptab, dim3((uint32_t)((n_ptab + 255) / 256)), dim3(256), 0, st, d.prefix, d.n_runs, d.P_enc, n_ptab, ptab);
   HIP_TRY(hipGetLastError());
   HIP_TRY(hipStreamSynchronize(st));
   d.bits = bits;
   d.cchunk = cchunk;
+  d.ptab = n_ptab ? ptab : nullptr;
   return HE_OK;
 }
 
