@@ -268,6 +268,56 @@ def mask_select_bench(he, ctx, torch, sizes=(25_600_000, 110_000_000, 1_300_000_
     return rows
 
 
+def fragmented_mask_bench(he, torch, P=110_000_000, ratio=0.1, reps=4):
+    """One client's round (encrypt, aggregate with weight 1, decrypt) on P parameters under masks of the same size and
+    different structure: the top `ratio` of a synthetic sensitivity map whose values are shared by `layer` consecutive
+    parameters plus 5 % per-parameter noise (layer = 1: a per-parameter selection, runs of one or two parameters), and
+    32 equal blocks.  Kernel times per round from the library's own events."""
+    ctx = he.Context(14, 4)
+    keys = he.he_keygen(ctx, 1)
+    g = torch.Generator(device="cuda").manual_seed(5)
+    w = torch.randn(P, generator=g, device="cuda") * 0.02
+    rows, k = [], 0
+
+    def probe(mask, tag):
+        ct = torch.empty((mask.n_ct, 2, 4, ctx.N), dtype=torch.int32, device="cuda")
+        pl = torch.empty(mask.n_plain, device="cuda")
+        ctg = torch.empty((mask.n_ct, 2, 3, ctx.N), dtype=torch.int32, device="cuda")
+        out = torch.empty(P, device="cuda")
+
+        def rnd():
+            he.he_encrypt_masked(ctx, keys, mask, 5, 0, w, ct, pl)
+            he.he_aggregate(ctx, [1.0], [ct], [pl], ctg, pl)
+            he.he_decrypt_merge(ctx, keys, mask, ctg, pl, out)
+        rnd()
+        torch.cuda.synchronize()
+        he.he_debug_timing_enable(ctx, True)
+        he.he_debug_timing_read(ctx)
+        for _ in range(reps):
+            rnd()
+        t = he.he_debug_timing_read(ctx)
+        he.he_debug_timing_enable(ctx, False)
+        rows.append({"mask": tag, "runs": int(he.load().he_mask_n_runs(mask.h)), "encrypted_params": mask.P_enc,
+                     "kernels_ms_per_round": {kk: v[0] / reps for kk, v in t.items() if v[1]},
+                     "max_abs_err": float((out - w).abs().max())})
+
+    for layer in (4096, 64, 1):
+        lay = torch.rand(P // layer + 1, generator=g, device="cuda").repeat_interleave(layer)[:P].contiguous()
+        sens = lay + 0.05 * torch.rand(P, generator=g, device="cuda")
+        del lay
+        m = he.he_mask_select_top(ctx, sens, ratio)
+        del sens
+        probe(m, f"top {ratio} of a map with layers of {layer}")
+        k = m.P_enc
+        m.close()
+    blk = he.he_mask_create(ctx, P, list(range(0, P, P // 32))[:32], [k // 32] * 32)
+    probe(blk, "32 blocks")
+    blk.close()
+    keys.close()
+    ctx.close()
+    return {"params": P, "ratio": ratio, "rows": rows}
+
+
 HEADLINE = "fm1p3b_sel5"          # the largest workload that runs whole on one GPU (32 clients x 1.3 B parameters)
 HEADLINE_MIN_FREE_GIB = 200       # what it needs resident; on a GPU with less free HBM the headline is bert_full
 OTHER_WORKLOADS = ("tiny_full", "resnet18_full", "resnet50_sel10", "bert_sel10", "bert_full")
@@ -597,6 +647,8 @@ def run_workload(he, si, torch, name, args, steps, warmup, headline, copy_gbs=No
             res["crypto_param_sweep"] = crypto_param_sweep(he, torch)
         if args.select_bench:
             res["mask_select"] = mask_select_bench(he, ctx, torch)
+        if args.fragmented_masks:
+            res["fragmented_masks"] = fragmented_mask_bench(he, torch)
         if args.issue_rates:
             res["issue_rates"] = issue_rates()
         if not args.no_cpu_baseline:
@@ -669,6 +721,8 @@ def main():
                     help="client_weighted: clients encode alpha_i * W_i, the server only adds ciphertexts (no rescale), one limb fewer")
     ap.add_argument("--param-sweep", action="store_true",
                     help="also run packing batch 1024..8192 x scaling bits 20/30 on a 1.66M-parameter vector, 3 clients")
+    ap.add_argument("--fragmented-masks", action="store_true",
+                    help="also time one client's round on 110 M parameters under top-p selections of different granularity and under blocks")
     ap.add_argument("--select-bench", action="store_true",
                     help="also time the encryption-mask selection (top-p of a sensitivity map) on 25.6M / 110M / 1.3B entries")
     ap.add_argument("--k-sweep", action="store_true",
