@@ -180,6 +180,31 @@ def test_mask_agreement_flow(he):
     assert ct.shape[0] == mask.n_ct and np.array_equal(plain.cpu().numpy(), w[~want])
 
 
+def test_fragmented_mask_on_unaligned_model_vectors(he):
+    """Compaction and merge of the remainder under a fragmented mask when the model vector and the output start at an odd
+    element of their allocations (the 16-byte accesses of the parameter-ordered kernels do not apply) and P is ragged."""
+    ctx = he.Context(11, 2)
+    keys = he.he_keygen(ctx, 3)
+    rs = np.random.default_rng(14)
+    for P in (4096 * 3 + 1, 4096 * 2, 70_001):
+        m = rs.random(P) < 0.3
+        mask = he.he_mask_from_bytes(ctx, torch.from_numpy(m.astype(np.uint8)).cuda())
+        full = torch.from_numpy(rs.normal(0, 0.02, P + 3).astype(np.float32)).cuda()
+        for off in (0, 1, 3):
+            w = full[off:off + P]
+            ct, pl = he.he_encrypt_masked(ctx, keys, mask, 9, 0, w)
+            assert torch.equal(pl, w[torch.from_numpy(~m).cuda()])
+            ct_g, pl_g = he.he_aggregate(ctx, [1.0], [ct], [pl])
+            out_full = torch.full((P + 3,), float("nan"), device="cuda")
+            out = he.he_decrypt_merge(ctx, keys, mask, ct_g, pl_g, out_full[off:off + P])
+            assert torch.equal(out[torch.from_numpy(~m).cuda()], pl)
+            assert float((out - w).abs().max()) < 1e-3                                   # masked entries: CKKS noise only
+            untouched = torch.ones(P + 3, dtype=torch.bool)
+            untouched[off:off + P] = False
+            assert bool(torch.isnan(out_full.cpu()[untouched]).all())                    # nothing written outside the vector
+        mask.close()
+
+
 def test_round_under_a_per_parameter_selection(he):
     """A whole round under the mask a top-p selection over per-parameter sensitivities gives: runs of one or two
     parameters (about 180 k of them here), so that a ciphertext's slots and a chunk of the remainder span thousands of
