@@ -123,8 +123,9 @@ void he_sk_destroy(he_sk* sk);
    n_runs = 0 is the empty mask (everything stays plaintext).  Synchronous.
    The mask object holds 32 bytes of device memory per run (masked and complement runs); a
    mask whose unencrypted runs average under 4096 parameters also holds a bit per parameter
-   and a word per 64 encrypted parameters (P / 8 + P_enc / 16 bytes), which the gather, the
-   compaction and the merge then use. */
+   and a word per 64 encrypted parameters (P / 8 + P_enc / 16 bytes): under such a mask
+   he_encrypt_masked and he_decrypt_merge go through the model once in parameter order, with a
+   packed copy of the encrypted parameters (4 bytes each) in the context's scratch. */
 he_status he_mask_create(he_ctx* ctx, uint64_t P, const uint64_t* starts_host,
                          const uint64_t* lens_host, uint64_t n_runs, he_mask** out);
 /* Builds the mask from a device byte mask (non-zero = encrypted).  The mask object's device

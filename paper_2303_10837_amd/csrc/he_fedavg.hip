@@ -51,6 +51,7 @@ struct MaskDev {
   const uint32_t* bits;     // bit i of the array = parameter i is masked; padded with ones to whole chunks of kBitChunk
   const uint64_t* cchunk;   // [P / kBitChunk + 2] unmasked parameters before parameter c * kBitChunk
   const uint32_t* ptab;     // [P_enc / 64 + 2] index of the masked run that holds packed position 64 k (the last entries: n_runs - 1)
+  const uint64_t* ident;    // {0, 0, P_enc}: run tables of the mask "the first P_enc entries of a vector of P_enc" (see k_merge_bits)
 };
 
 constexpr uint32_t kBitChunk = 4096;  // parameters per workgroup of the bit-mask compaction (256 threads x 16)
@@ -947,6 +948,73 @@ k_plain_move_bits(MaskDev mk, const float* __restrict__ src, float* __restrict__
   }
 }
 
+// Both halves of a model vector in one pass (encrypt side of a fragmented mask): the unmasked parameters go to the
+// compacted remainder, the masked ones to the packed slot vector that the encoder then reads as a plain array.  Same
+// walk as k_plain_move_bits; the masked values fill the staging array from its end.  MERGE is the inverse (decrypt side):
+// the decoded slot vector and the aggregated remainder are woven back into the model, every parameter written once.
+template <bool MERGE>
+__global__ void __launch_bounds__(256)
+k_split_bits(MaskDev mk, const float* __restrict__ model_in, float* __restrict__ model_out, const float* __restrict__ packed_in,
+             float* __restrict__ packed_out, const float* __restrict__ plain_in, float* __restrict__ plain_out) {
+  __shared__ float stage[kBitChunk];
+  const uint64_t chunk = blockIdx.x;
+  const uint64_t i0 = chunk * kBitChunk + (uint64_t)threadIdx.x * 16;  // the thread's first parameter
+  const uint32_t word = mk.bits[chunk * (kBitChunk / 32) + (threadIdx.x >> 1)];
+  const uint32_t half = (word >> (16 * (threadIdx.x & 1))) & 0xFFFFu;
+  const uint32_t valid = i0 >= mk.P ? 0u : (mk.P - i0 >= 16 ? 0xFFFFu : ((1u << (uint32_t)(mk.P - i0)) - 1u));
+  const uint32_t um = ~half & 0xFFFFu, mm = half & valid;  // unmasked / masked among the thread's parameters (padding is neither)
+  uint32_t totals;
+  const uint32_t excl = he_sel::block_exclusive_scan((uint32_t)__popc(um) | ((uint32_t)__popc(mm) << 16), &totals);  // both counts <= 4096
+  uint32_t ru = excl & 0xFFFFu, rm = excl >> 16;
+  const uint32_t total_u = totals & 0xFFFFu, total_m = totals >> 16;
+  const uint64_t cbase = mk.cchunk[chunk], mbase = chunk * kBitChunk - cbase;  // every parameter before the chunk is below P
+  const bool wide = i0 + 16 <= mk.P && (reinterpret_cast<uintptr_t>(MERGE ? (const void*)model_out : (const void*)model_in) & 15u) == 0;
+  if (!MERGE) {
+    float x[16];
+    if (wide) {
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const v4f_a16 q4 = __builtin_nontemporal_load(reinterpret_cast<const v4f_a16*>(model_in + i0) + v);
+        x[4 * v] = q4.x; x[4 * v + 1] = q4.y; x[4 * v + 2] = q4.z; x[4 * v + 3] = q4.w;
+      }
+    } else {
+#pragma unroll
+      for (int b = 0; b < 16; ++b) x[b] = ((valid >> b) & 1u) ? model_in[i0 + b] : 0.f;
+    }
+#pragma unroll
+    for (int b = 0; b < 16; ++b) {
+      if ((um >> b) & 1u) stage[ru++] = x[b];
+      else if ((mm >> b) & 1u) stage[kBitChunk - 1 - rm++] = x[b];
+    }
+    __syncthreads();
+    for (uint32_t j = threadIdx.x; j < total_u; j += 256) __builtin_nontemporal_store(stage[j], plain_out + cbase + j);
+    for (uint32_t j = threadIdx.x; j < total_m; j += 256) packed_out[mbase + j] = stage[kBitChunk - 1 - j];  // read again soon: keep in L2
+  } else {
+    for (uint32_t j = threadIdx.x; j < total_u; j += 256) stage[j] = __builtin_nontemporal_load(plain_in + cbase + j);
+    for (uint32_t j = threadIdx.x; j < total_m; j += 256) stage[kBitChunk - 1 - j] = packed_in[mbase + j];
+    __syncthreads();
+    float x[16];
+#pragma unroll
+    for (int b = 0; b < 16; ++b) {
+      x[b] = 0.f;
+      if ((um >> b) & 1u) x[b] = stage[ru++];
+      else if ((mm >> b) & 1u) x[b] = stage[kBitChunk - 1 - rm++];
+    }
+    if (wide) {
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        v4f_a16 q4;
+        q4.x = x[4 * v]; q4.y = x[4 * v + 1]; q4.z = x[4 * v + 2]; q4.w = x[4 * v + 3];
+        *(reinterpret_cast<v4f_a16*>(model_out + i0) + v) = q4;
+      }
+    } else {
+#pragma unroll
+      for (int b = 0; b < 16; ++b)
+        if ((valid >> b) & 1u) model_out[i0 + b] = x[b];
+    }
+  }
+}
+
 template <bool SCATTER>
 void launch_plain_move(const MaskDev& mk, const float* src, float* dst, hipStream_t st) {
   if (mk.bits) {
@@ -1729,7 +1797,8 @@ he_status build_mask_bits(he_mask* mk, hipStream_t st) {
   const size_t cnt_bytes = ((n_pchunks * sizeof(uint32_t) + 255) / 256) * 256;
   const size_t off_bytes = (((n_pchunks + 2) * sizeof(uint64_t) + 255) / 256) * 256;
   const uint64_t n_ptab = d.n_runs ? d.P_enc / 64 + 2 : 0;  // the run of every 64th packed position, for gather and scatter
-  if (hipMalloc(&mk->bits_block, bits_bytes + cnt_bytes + off_bytes + n_ptab * sizeof(uint32_t)) != hipSuccess) {
+  const size_t ptab_bytes = ((n_ptab * sizeof(uint32_t) + 255) / 256) * 256;
+  if (hipMalloc(&mk->bits_block, bits_bytes + cnt_bytes + off_bytes + ptab_bytes + 3 * sizeof(uint64_t)) != hipSuccess) {
     (void)hipGetLastError();
     mk->bits_block = nullptr;
     return HE_OK;
@@ -1745,10 +1814,14 @@ he_status build_mask_bits(he_mask* mk, hipStream_t st) {
   if (n_ptab)
     hipLaunchKernelGGL(k_mask_ptab, dim3((uint32_t)((n_ptab + 255) / 256)), dim3(256), 0, st, d.prefix, d.n_runs, d.P_enc, n_ptab, ptab);
   HIP_TRY(hipGetLastError());
+  uint64_t* ident = reinterpret_cast<uint64_t*>(base + bits_bytes + cnt_bytes + off_bytes + ptab_bytes);
+  const uint64_t ident_host[3] = {0, 0, d.P_enc};
+  HIP_TRY(hipMemcpyAsync(ident, ident_host, sizeof(ident_host), hipMemcpyHostToDevice, st));
   HIP_TRY(hipStreamSynchronize(st));
   d.bits = bits;
   d.cchunk = cchunk;
   d.ptab = n_ptab ? ptab : nullptr;
+  d.ident = ident;
   return HE_OK;
 }
 
@@ -2315,6 +2388,17 @@ static he_status encrypt_masked_impl(he_ctx* ctx, const he_pk* pk, const he_mask
     s = ensure_ws(ctx, chunk * N * kEncScratchBytesPerCoeff);
     if (s != HE_OK) return s;
   }
+  // Under a fragmented mask one pass in parameter order fills the remainder and the packed slot vector (n_ct * n floats,
+  // zero-padded), which the encoder then reads as a plain array; the static-scratch form keeps the gather.
+  const uint64_t n_slots = N / 2;
+  const size_t enc_scratch_bytes = ((chunk * N * kEncScratchBytesPerCoeff + 255) / 256) * 256;
+  const bool split = mk.bits && !fixed_scratch && n_ct > 0;
+  float* packed = nullptr;
+  if (split) {
+    s = ensure_ws(ctx, enc_scratch_bytes + n_ct * n_slots * sizeof(float));
+    if (s != HE_OK) return s;
+    packed = reinterpret_cast<float*>(static_cast<char*>(ctx->ws) + enc_scratch_bytes);
+  }
   const EncScratch sc = carve_enc_scratch(fixed_scratch ? fixed_scratch : ctx->ws, chunk, N);
   // The remainder is compacted first, on the same stream: an HBM-bound copy beside the transform kernels (tried on a
   // second stream, and on a disjoint set of compute units) lengthens them by as much as it saves, because it evicts
@@ -2322,7 +2406,14 @@ static he_status encrypt_masked_impl(he_ctx* ctx, const he_pk* pk, const he_mask
   if (n_plain) {
     {
       KernelTimer timer_(ctx, KID_PLAIN_MOVE, st);
-      launch_plain_move<false>(mk, w_dev, plain_out_dev, st);
+      if (split) {
+        const uint64_t n_pchunks = (mk.P + kBitChunk - 1) / kBitChunk, pad = n_ct * n_slots - mk.P_enc;
+        hipLaunchKernelGGL(k_split_bits<false>, dim3((uint32_t)n_pchunks), dim3(256), 0, st, mk, w_dev, (float*)nullptr,
+                           (const float*)nullptr, packed, (const float*)nullptr, plain_out_dev);
+        if (pad) hipLaunchKernelGGL(k_fill_u32, dim3(grid_for(pad, 256, 64)), dim3(256), 0, st, reinterpret_cast<uint32_t*>(packed + mk.P_enc), pad, 0u);
+      } else {
+        launch_plain_move<false>(mk, w_dev, plain_out_dev, st);
+      }
       HIP_TRY(hipGetLastError());
     }
     if (pre_scale != 1.0) {  // weigh the compacted remainder in place: float32(alpha * x), product in float64
@@ -2336,7 +2427,7 @@ static he_status encrypt_masked_impl(he_ctx* ctx, const he_pk* pk, const he_mask
   }
   for (uint64_t c0 = 0; c0 < n_ct; c0 += chunk) {
     const uint64_t cn = std::min<uint64_t>(chunk, n_ct - c0);
-    s = launch_encode(ctx, mk, w_dev, nullptr, c0, cn, sc.m, &sc, seed, client_id, st, pre_scale);
+    s = launch_encode(ctx, mk, w_dev, split ? packed + c0 * n_slots : nullptr, c0, cn, sc.m, &sc, seed, client_id, st, pre_scale);
     if (s != HE_OK) return s;
     s = launch_encrypt(ctx, pk, cn, sc.m, sc, ct_out_dev + c0 * 2 * rg.L * N, st);
     if (s != HE_OK) return s;
@@ -2552,12 +2643,24 @@ static he_status decrypt_merge_impl(he_ctx* ctx, const he_sk* sk, const he_mask*
   if (level < 1 || level > rg.L) return fail(HE_ERR_LEVEL, "level must be in 1..L");
   const uint64_t chunk = std::min<uint64_t>(kCtChunk, n_ct);
   const size_t N = rg.N;
+  // Under a fragmented mask the decoder writes the packed slot vector (as under the mask "the first P_enc entries"),
+  // and one pass in parameter order weaves it and the remainder into the model.
+  const bool weave = mk.bits && n_ct > 0 && n_plain > 0;
+  const size_t d_bytes = ((chunk * level * N * 4 + 255) / 256) * 256;
   if (chunk) {
-    s = ensure_ws(ctx, chunk * level * N * 4);
+    s = ensure_ws(ctx, d_bytes + (weave ? mk.P_enc * sizeof(float) : 0));
     if (s != HE_OK) return s;
   }
   uint32_t* d = static_cast<uint32_t*>(ctx->ws);
-  if (n_plain) {  // the scatter of the remainder writes other entries than the decoder does
+  float* packed = weave ? reinterpret_cast<float*>(static_cast<char*>(ctx->ws) + d_bytes) : nullptr;
+  MaskDev first_entries{};
+  if (weave) {
+    first_entries.start = mk.ident;
+    first_entries.prefix = mk.ident + 1;
+    first_entries.n_runs = 1;
+    first_entries.P = first_entries.P_enc = mk.P_enc;
+  }
+  if (n_plain && !weave) {  // the scatter of the remainder writes other entries than the decoder does
     KernelTimer timer_(ctx, KID_PLAIN_MOVE, st);
     launch_plain_move<true>(mk, plain_glob_dev, w_out_dev, st);
     HIP_TRY(hipGetLastError());
@@ -2566,8 +2669,15 @@ static he_status decrypt_merge_impl(he_ctx* ctx, const he_sk* sk, const he_mask*
     const uint64_t cn = std::min<uint64_t>(chunk, n_ct - c0);
     s = launch_decrypt(ctx, sk, ct_glob_dev + c0 * 2 * level * N, cn, level, d, st);
     if (s != HE_OK) return s;
-    s = launch_decode(ctx, level, mk, d, c0, cn, w_out_dev, nullptr, st);
+    s = launch_decode(ctx, level, weave ? first_entries : mk, d, c0, cn, weave ? packed : w_out_dev, nullptr, st);
     if (s != HE_OK) return s;
+  }
+  if (weave) {
+    KernelTimer timer_(ctx, KID_PLAIN_MOVE, st);
+    const uint64_t n_pchunks = (mk.P + kBitChunk - 1) / kBitChunk;
+    hipLaunchKernelGGL(k_split_bits<true>, dim3((uint32_t)n_pchunks), dim3(256), 0, st, mk, (const float*)nullptr, w_out_dev,
+                       (const float*)packed, (float*)nullptr, plain_glob_dev, (float*)nullptr);
+    HIP_TRY(hipGetLastError());
   }
   return HE_OK;
 } catch (...) {
