@@ -32,8 +32,9 @@ def test_static_scratch_entry_point_matches_the_allocating_one(he, log2_n, limbs
     n = ctx.n_slots
     big = (7 * n + 1234 + 3 * n, [(5, 3 * n + 17), (4 * n, 2 * n), (7 * n + 100, n + 500)])      # 7 ciphertexts, ragged tail
     small = (2 * n + 99, [(n // 2, n + 3)])                                                      # 2 ciphertexts
+    frag = (6 * n + 5, [(i * 37 + 2, 11) for i in range((6 * n) // 37)])                         # runs of 11 every 37: the fragmented-mask kernels
     torch.cuda.synchronize()
-    for P, runs in (big, small):
+    for P, runs in (big, frag, small):
         w = torch.from_numpy(rs.normal(0, 0.05, P).astype(np.float32)).cuda()
         m_ref, m = _mask(he, ref_ctx, P, runs), _mask(he, ctx, P, runs)
         ct_ref, pl_ref = he.he_encrypt_masked(ref_ctx, ref_keys, m_ref, SEED + 1, 4, w)
