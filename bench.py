@@ -778,6 +778,11 @@ def main():
             rows[other]["config"] = {k: r["config"][k] for k in ("clients", "params_per_client", "encrypted_params", "n_ct_per_client",
                                                                   "ring_degree", "limbs", "streamed_clients")}
         res["workloads"] = rows
+        if "fragmented_masks" not in res:      # beside the block masks of the workloads: the masks a per-parameter selection gives
+            try:
+                res["fragmented_masks"] = fragmented_mask_bench(he, torch)
+            except Exception as e:             # a side figure never costs the run its result line
+                res["fragmented_masks"] = {"error": f"{type(e).__name__}: {e}"}
     print(json.dumps(res))
 
 
