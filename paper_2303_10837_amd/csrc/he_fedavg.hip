@@ -426,8 +426,12 @@ k_encrypt_s(RingDev rg, const uint2* __restrict__ pk, const int8_t* __restrict__
   // 512 KiB instead of 2 MiB at N = 2^14, L = 4, but reads the inputs on L XCDs) and 2 % faster.
   const uint32_t slot = blockIdx.x >> 3, xcd = blockIdx.x & 7;
   const uint32_t j = slot % L;
-  const uint64_t c = (uint64_t)(slot / L) * 8 + xcd;
-  if (c >= n_ct) return;  // whole workgroup leaves before any barrier
+  const uint64_t c_lin = (uint64_t)(slot / L) * 8 + xcd;
+  if (c_lin >= n_ct) return;  // whole workgroup leaves before any barrier
+  // Last ciphertext first: the encoder has just written this launch's inputs in ascending order (235 MB per 2048
+  // ciphertexts at N = 2^14, about what the last-level cache holds), so the ones written last are the ones still cached
+  // when this kernel starts; going through them in the encoder's order measured 1.8 % slower.
+  const uint64_t c = n_ct - 1 - c_lin;
   const uint32_t q = rg.q[j];
   const uint2* twf = rg.tw_fwd + (size_t)j * N;
   const uint2* twi = rg.tw_inv + (size_t)j * N;
