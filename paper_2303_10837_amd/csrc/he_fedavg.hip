@@ -815,6 +815,27 @@ k_plain_move(MaskDev mk, const float* __restrict__ src, float* __restrict__ dst)
   if (t0 >= t1) return;
   const uint32_t lo = run_find(mk.cprefix, mk.n_cruns, t0);
   const uint32_t hi = run_find(mk.cprefix, mk.n_cruns, t1 - 1);
+  if (VEC && lo == hi && t1 - t0 == kMoveChunk) {
+    // The whole chunk lies in one run (all but a few chunks of a block-structured mask): a shifted copy, the four
+    // 16-byte loads of a thread issued before its stores.
+    const uint64_t shift = mk.cstart[lo] - mk.cprefix[lo];  // model index = compacted position + shift
+    const float* model_in = SCATTER ? nullptr : src + shift;
+    float* model_out = SCATTER ? dst + shift : nullptr;
+    v4f_a16 v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const uint64_t t = t0 + 4 * ((uint64_t)threadIdx.x + 256 * k);
+      if (SCATTER) v[k] = __builtin_nontemporal_load(reinterpret_cast<const v4f_a16*>(src + t));
+      else v[k] = __builtin_nontemporal_load(reinterpret_cast<const v4f_a4*>(model_in + t));
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const uint64_t t = t0 + 4 * ((uint64_t)threadIdx.x + 256 * k);
+      if (SCATTER) *reinterpret_cast<v4f_a4*>(model_out + t) = v[k];
+      else __builtin_nontemporal_store(v[k], reinterpret_cast<v4f_a16*>(dst + t));
+    }
+    return;
+  }
   if (VEC) {
 #pragma unroll 4
     for (uint64_t t = t0 + 4 * (uint64_t)threadIdx.x; t < t1; t += 4 * 256) {
